@@ -1,0 +1,338 @@
+"""Pins for the CPU oracle: what the paper and plain arithmetic fix about the
+Endor format, checked without any reference to the GPU library.
+
+Sources: Algorithm 1 / Algorithm 2 and the size example of Section 4.1, the
+8-bit example of Section 4.2, the CSR remark of Section 2.1, the losslessness
+statement of Section 5.3, "any sparsity pattern and ratio" of Section 5.5.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import endor_oracle as orc
+from paper_2406_11674_amd import synth
+
+
+# --------------------------------------------------------------------------
+# hand-built matrices: expected bytes typed by hand from the format statement
+# --------------------------------------------------------------------------
+def _u16(rows):
+    return np.array(rows, dtype=np.uint16)
+
+
+HAND_CASES = [
+    # name, dense (bit patterns), bitmap bytes, values, row_offsets
+    ("1x8 first element only",
+     _u16([[0x3C00, 0, 0, 0, 0, 0, 0, 0]]), [0x01], [0x3C00], [0, 1]),
+    ("1x8 last element only",
+     _u16([[0, 0, 0, 0, 0, 0, 0, 0xBC00]]), [0x80], [0xBC00], [0, 1]),
+    ("2x8 alternating, rows in phase opposition",
+     _u16([[1, 0, 2, 0, 3, 0, 4, 0], [0, 5, 0, 6, 0, 7, 0, 8]]),
+     [0x55, 0xAA], [1, 2, 3, 4, 5, 6, 7, 8], [0, 4, 8]),
+    # 3x5: N = 15, rows straddle a byte boundary, one pad bit (bit 7 of byte 1)
+    # flat bits e=0..14: 1 0 0 1 1 | 0 0 0 0 0 | 1 1 0 0 1
+    #   byte0 = e0..7  = 1,0,0,1,1,0,0,0 -> 0b00011001 = 0x19
+    #   byte1 = e8..14 = 0,0,1,1,0,0,1,(pad 0) -> 0b01001100 = 0x4C
+    ("3x5 rows straddling a byte, zero row in the middle",
+     _u16([[10, 0, 0, 11, 12], [0, 0, 0, 0, 0], [13, 14, 0, 0, 15]]),
+     [0x19, 0x4C], [10, 11, 12, 13, 14, 15], [0, 3, 3, 6]),
+    # 2x3 non-symmetric positions so a column-major walk gives another answer
+    # flat: 7 0 8 | 9 0 0 -> bits 1,0,1,1,0,0 -> 0b00001101 = 0x0D
+    # (a column-major walk would give v = 7 9 8)
+    ("2x3 order of values is row-major",
+     _u16([[7, 0, 8], [9, 0, 0]]), [0x0D], [7, 8, 9], [0, 2, 3]),
+    # fp16 special patterns are all non-zero patterns: -0.0, smallest subnormal, +Inf, a NaN
+    ("1x6 special fp16 patterns are kept",
+     _u16([[0x8000, 0x0001, 0, 0x7C00, 0x7E01, 0]]), [0x1B], [0x8000, 0x0001, 0x7C00, 0x7E01], [0, 4]),
+]
+
+
+@pytest.mark.parametrize("name,dense,bm,vals,roffs", HAND_CASES, ids=[c[0] for c in HAND_CASES])
+def test_hand_built_compress(name, dense, bm, vals, roffs):
+    b, v, r = orc.compress(dense)
+    assert b.tolist() == bm
+    assert v.tolist() == vals
+    assert r.tolist() == roffs
+
+
+@pytest.mark.parametrize("name,dense,bm,vals,roffs", HAND_CASES, ids=[c[0] for c in HAND_CASES])
+def test_hand_built_decompress(name, dense, bm, vals, roffs):
+    rows, cols = dense.shape
+    out = orc.decompress(rows, cols, np.array(bm, np.uint8), np.array(vals, np.uint16))
+    assert out.dtype == np.uint16 and out.shape == dense.shape
+    assert np.array_equal(out, dense)
+    assert orc.row_offsets(rows, cols, np.array(bm, np.uint8)).tolist() == roffs
+
+
+def test_pad_bits_are_ignored_on_decompress():
+    # 3x5 case with the pad bit (bit 7 of byte 1) set: same output, no extra value read.
+    dense = HAND_CASES[3][1]
+    out = orc.decompress(3, 5, np.array([0x19, 0x4C | 0x80], np.uint8),
+                         np.array([10, 11, 12, 13, 14, 15], np.uint16))
+    assert np.array_equal(out, dense)
+
+
+def test_hand_cases_tell_the_readings_apart():
+    """The fixtures above must fail for the plausible wrong readings: MSB-first
+    bit order, column-major value order, per-row padding of the bitmap, and a
+    counter that restarts at every row of a single value array."""
+    dense = HAND_CASES[3][1]                       # 3x5
+    nz = dense != 0
+    msb = np.packbits(nz.reshape(-1), bitorder="big").tolist()
+    assert msb != HAND_CASES[3][2]
+    padded = np.packbits(nz, axis=1, bitorder="little").reshape(-1).tolist()
+    assert padded != HAND_CASES[3][2]
+    d23 = HAND_CASES[4][1]
+    colmajor = d23.T[d23.T != 0].tolist()
+    assert colmajor != HAND_CASES[4][3]
+    # k reset to 0 at each row while indexing one array v: row 1 of 2x8 would
+    # receive v[0..3] again instead of v[4..7]
+    d28 = HAND_CASES[2][1]
+    v = np.array(HAND_CASES[2][3], np.uint16)
+    wrong_row1 = np.zeros(8, np.uint16)
+    wrong_row1[d28[1] != 0] = v[:4]
+    assert not np.array_equal(wrong_row1, d28[1])
+
+
+# --------------------------------------------------------------------------
+# reduction to library routines (numpy packbits / boolean-mask scatter)
+# --------------------------------------------------------------------------
+SHAPES = [(1, 1), (1, 7), (1, 8), (1, 9), (3, 5), (5, 3), (7, 13), (16, 64), (33, 65),
+          (64, 63), (2, 4095), (2, 4096), (2, 4097), (129, 257), (1, 70000)]
+
+
+def _random_dense(rows, cols, keep, seed):
+    g = np.random.default_rng(seed)
+    w = g.integers(1, 1 << 16, size=(rows, cols), dtype=np.uint32).astype(np.uint16)
+    w[g.random((rows, cols)) >= keep] = 0
+    return w
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.1, 0.5, 0.9, 1.0])
+def test_compress_equals_numpy_reduction(shape, keep):
+    rows, cols = shape
+    w = _random_dense(rows, cols, keep, seed=rows * 1000 + cols)
+    b, v, r = orc.compress(w)
+    nz = (w != 0).reshape(-1)
+    assert np.array_equal(b, np.packbits(nz, bitorder="little"))
+    assert np.array_equal(v, w.reshape(-1)[nz])
+    assert np.array_equal(r, np.concatenate([[0], np.cumsum((w != 0).sum(axis=1))]))
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.3, 0.5, 1.0])
+def test_decompress_equals_numpy_mask_scatter(shape, keep):
+    rows, cols = shape
+    n = rows * cols
+    g = np.random.default_rng(n + 17)
+    bits = g.random(n) < keep
+    bitmap = np.packbits(bits, bitorder="little")
+    # any 16-bit pattern may sit in v, the zero pattern included (decompression never inspects values)
+    values = g.integers(0, 1 << 16, size=int(bits.sum()), dtype=np.uint32).astype(np.uint16)
+    if values.size:
+        values[0] = 0
+    expect = np.zeros(n, np.uint16)
+    expect[np.unpackbits(bitmap, bitorder="little")[:n] == 1] = values
+    out = orc.decompress(rows, cols, bitmap, values)
+    assert np.array_equal(out.reshape(-1), expect)
+
+
+# --------------------------------------------------------------------------
+# invariants the paper states
+# --------------------------------------------------------------------------
+def _special_dense(rows, cols, seed):
+    g = np.random.default_rng(seed)
+    w = _random_dense(rows, cols, 0.5, seed)
+    specials = np.array([0x8000, 0x0001, 0x03FF, 0x7C00, 0xFC00, 0x7E00, 0xFFFF, 0x0400], np.uint16)
+    idx = g.integers(0, rows * cols, size=max(1, rows * cols // 10))
+    w.reshape(-1)[idx] = specials[g.integers(0, specials.size, size=idx.size)]
+    return w
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+def test_round_trip_is_lossless_bit_for_bit(shape):
+    rows, cols = shape
+    w = _special_dense(rows, cols, seed=cols)
+    b, v, r = orc.compress(w)
+    assert np.array_equal(orc.decompress(rows, cols, b, v), w)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+def test_counting_invariants(shape):
+    rows, cols = shape
+    n = rows * cols
+    w = _special_dense(rows, cols, seed=rows)
+    b, v, r = orc.compress(w)
+    nnz = int(np.count_nonzero(w))
+    assert b.size == (n + 7) // 8
+    assert int(np.unpackbits(b).sum()) == nnz == v.size == r[-1]
+    assert not np.any(v == 0)
+    assert np.all(np.diff(r) >= 0)
+    assert np.array_equal(np.diff(r), (w != 0).sum(axis=1))
+    if n % 8:
+        assert b[-1] >> (n % 8) == 0                      # pad bits are zero
+    assert b.nbytes + v.nbytes == (n + 7) // 8 + 2 * nnz  # compressed size, fp16
+
+
+def test_reverse_identity():
+    g = np.random.default_rng(5)
+    rows, cols = 37, 91
+    n = rows * cols
+    bits = g.random(n) < 0.4
+    bitmap = np.packbits(bits, bitorder="little")
+    values = g.integers(1, 1 << 16, size=int(bits.sum()), dtype=np.uint32).astype(np.uint16)
+    dense = orc.decompress(rows, cols, bitmap, values)
+    b2, v2, _ = orc.compress(dense)
+    assert np.array_equal(b2, bitmap) and np.array_equal(v2, values)
+
+
+def test_special_cases():
+    rows, cols = 9, 50
+    n = rows * cols
+    nb = (n + 7) // 8
+    # all bits 0: output all zero, values empty
+    out = orc.decompress(rows, cols, np.zeros(nb, np.uint8), np.zeros(0, np.uint16))
+    assert not out.any()
+    # all bits 1: output is v itself
+    v = np.arange(1, n + 1, dtype=np.uint16)
+    ones = np.packbits(np.ones(n, bool), bitorder="little")
+    assert np.array_equal(orc.decompress(rows, cols, ones, v).reshape(-1), v)
+    # a single set bit anywhere
+    for e in (0, 1, 7, 8, 63, 64, n - 1):
+        bm = np.zeros(nb, np.uint8)
+        bm[e >> 3] = 1 << (e & 7)
+        out = orc.decompress(rows, cols, bm, np.array([0xABCD], np.uint16)).reshape(-1)
+        assert out[e] == 0xABCD and np.count_nonzero(out) == 1
+
+
+def test_values_too_short_is_refused():
+    with pytest.raises(ValueError):
+        orc.decompress(1, 8, np.array([0xFF], np.uint8), np.zeros(7, np.uint16))
+
+
+# --------------------------------------------------------------------------
+# the paper's printed sizes (Section 4.1 and Section 4.2)
+# --------------------------------------------------------------------------
+def _golden(golden_dir):
+    d = {}
+    with open(os.path.join(golden_dir, "size_example.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = [s.strip() for s in line.split("=")]
+                d[k] = float(v)
+    return d
+
+
+def _two_sig(x):
+    """Round to two significant figures, the precision the paper prints sizes at."""
+    from decimal import Decimal, ROUND_HALF_EVEN
+    d = Decimal(repr(float(x)))
+    q = Decimal(1).scaleb(d.adjusted() - 1)
+    return float(d.quantize(q, rounding=ROUND_HALF_EVEN))
+
+
+def test_paper_size_example_closed_form(golden_dir):
+    g = _golden(golden_dir)
+    rows, cols = int(g["rows"]), int(g["cols"])
+    n = rows * cols
+    nnz = int(n * g["keep_fraction"])
+    bitmap = orc.bitmap_bytes(rows, cols)
+    assert bitmap == 42_467_328 and 2 * n == 679_477_248 and 2 * nnz == 339_738_624
+    # the paper prints decimal megabytes to two significant figures
+    assert _two_sig(2 * n / 1e6) == g["fp16_dense_MB"]
+    assert _two_sig(2 * nnz / 1e6) == g["fp16_values_MB"]
+    assert _two_sig(bitmap / 1e6) == g["bitmap_MB"]
+    assert (bitmap + 2 * nnz) / (2 * n) == 1 / 16 + 1 / 2
+    assert _two_sig(100 * (bitmap + 2 * nnz) / (2 * n)) == g["fp16_ratio_percent"]
+    # 8-bit elements: same bitmap, one byte per value; 1/8 + 1/2 = 0.625 is printed as 62 %
+    assert _two_sig(n / 1e6) == g["int8_dense_MB"]
+    assert _two_sig(nnz / 1e6) == g["int8_values_MB"]
+    assert (bitmap + nnz) / n == 1 / 8 + 1 / 2
+    assert _two_sig(100 * (bitmap + nnz) / n) == g["int8_ratio_percent"]
+
+
+def test_paper_size_example_on_a_scaled_down_matrix():
+    """Same 1/16 + p law measured on real oracle output (exactly half kept)."""
+    rows, cols = 96, 384
+    w = np.zeros((rows, cols), np.uint16)
+    w.reshape(-1)[np.random.default_rng(1).permutation(rows * cols)[: rows * cols // 2]] = 0x3555
+    b, v, _ = orc.compress(w)
+    assert (b.nbytes + v.nbytes) / w.nbytes == 0.5625
+    w8 = w.astype(np.uint8)  # 0x55 where kept
+    b8, v8, _ = orc.compress(w8)
+    assert np.array_equal(b8, b)
+    assert (b8.nbytes + v8.nbytes) / w8.nbytes == 0.625
+
+
+def test_csr_gives_no_compression_at_half_sparsity():
+    # Section 2.1: with a 2-byte column index per 2-byte non-zero, the index data
+    # at 50 % sparsity is as large as the zeros that were removed.
+    n, nnz = 9216 * 36864, 9216 * 36864 // 2
+    assert 2 * nnz + 2 * nnz == 2 * n
+
+
+# --------------------------------------------------------------------------
+# derived tables and variants
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("tile", [1, 8, 64, 100, 4096])
+def test_tile_offsets_equal_cumsum(tile):
+    n = 3 * 4096 + 123
+    bits = np.random.default_rng(tile).random(n) < 0.5
+    bitmap = np.packbits(bits, bitorder="little")
+    offs = orc.tile_offsets(n, tile, bitmap)
+    cs = np.concatenate([[0], np.cumsum(bits)])
+    ntiles = (n + tile - 1) // tile
+    expect = [cs[min(t * tile, n)] for t in range(ntiles + 1)]
+    assert offs.tolist() == expect
+
+
+def test_selected_rows_equal_gather_of_full_output():
+    rows, cols = 40, 77
+    w = _random_dense(rows, cols, 0.5, 3)
+    b, v, r = orc.compress(w)
+    sel = np.array([39, 0, 5, 5, 17], np.int64)
+    out = orc.decompress_selected_rows(cols, sel, r, b, v)
+    assert np.array_equal(out, w[sel])
+
+
+def test_threaded_equals_sequential():
+    rows, cols = 67, 129
+    w = _random_dense(rows, cols, 0.5, 4)
+    b, v, r = orc.compress(w)
+    for threads in (1, 2, 3, 8, 100):
+        assert np.array_equal(orc.decompress_threaded(rows, cols, b, v, r, threads), w)
+
+
+def test_int8_variant_round_trip_and_numpy():
+    w = synth.pruned_int8(33, 70, 0.5, seed=9)
+    b, v, r = orc.compress(w)
+    nz = (w != 0).reshape(-1)
+    assert v.dtype == np.uint8
+    assert np.array_equal(b, np.packbits(nz, bitorder="little"))
+    assert np.array_equal(v, w.reshape(-1)[nz])
+    assert np.array_equal(orc.decompress(33, 70, b, v), w)
+
+
+# --------------------------------------------------------------------------
+# the synthetic input recipe
+# --------------------------------------------------------------------------
+def test_synth_recipe():
+    w = synth.pruned_fp16(512, 1024, keep=0.5, seed=synth.seed_for(0, 0))
+    assert w.dtype == np.uint16
+    kept = w != 0
+    assert not np.any((w & 0x7FFF == 0) & kept)            # no +-0 among kept elements
+    frac = kept.mean()
+    assert abs(frac - 0.5) < 0.01
+    x = w.view(np.float16)[kept].astype(np.float64)
+    assert abs(x.mean()) < 1e-3 and abs(x.std() - 0.02) < 1e-3
+    # thread count does not change the result; the seed does
+    assert np.array_equal(w, synth.pruned_fp16(512, 1024, 0.5, synth.seed_for(0, 0), threads=1))
+    big = synth.pruned_fp16(9000, 1024, 0.5, 7, threads=1)
+    assert np.array_equal(big, synth.pruned_fp16(9000, 1024, 0.5, 7, threads=4))
+    assert not np.array_equal(w, synth.pruned_fp16(512, 1024, 0.5, synth.seed_for(0, 1)))
+    sk = synth.pruned_fp16(2048, 512, 0.5, 11, row_skew=True)
+    per_row = (sk != 0).mean(axis=1)
+    assert abs(per_row.mean() - 0.5) < 0.02 and 0.18 < per_row.std() < 0.27   # Beta(2,2): sd 0.2236
