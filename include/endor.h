@@ -1,0 +1,169 @@
+/*
+ * endor.h -- C ABI of the MI355X (gfx950) library for the Endor bitmap sparse
+ * format: host-side compression and on-GPU decompression of an unstructured-
+ * sparse weight matrix.
+ *
+ * THE FORMAT (paper: Figure "Sparse format" and Section 4.1; Algorithm 1 and
+ * Algorithm 2).  A rows x cols matrix W of 16-bit elements (fp16 in the paper;
+ * the library treats them as opaque bit patterns) is stored as
+ *
+ *   bitmap   one bit per element, a single 1-d bit vector over the row-major
+ *            flat index e = i*cols + j.  Bit e is bit (e & 7) of byte (e >> 3),
+ *            i.e. bit (e & 63) of little-endian 64-bit word (e >> 6).  There is
+ *            no per-row padding.  The buffer is endor_bitmap_bytes() long
+ *            (ceil(rows*cols/64) whole 64-bit words); pad bits past rows*cols
+ *            are written as 0 by endor_compress and ignored by everything else.
+ *   values   the elements whose bit is 1, in row-major order, packed; nnz of
+ *            them (nnz == number of 1 bits).
+ *
+ * An element is "non-zero" when its bit pattern is not all zero, so -0.0,
+ * subnormals, Inf and NaN are values like any other and a round trip is exact
+ * bit for bit.  Decompression writes the all-zero pattern where the bit is 0 and
+ * never inspects the values it places.
+ *
+ * CONVENTIONS.  Every function returns an endor_status (0 = ok); none throws,
+ * aborts or prints.  The library never allocates, frees or keeps caller memory
+ * and has no mutable global state.  "host" pointers are ordinary CPU memory;
+ * "device" pointers are HIP device memory on the current device.  Device entry
+ * points only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without synchronising; argument errors are found
+ * on the host before anything is launched.  rows == 0 or cols == 0 is valid and
+ * does nothing.  rows*cols must be below 2^34.
+ *
+ * Alignment: d_bitmap 8 bytes.  d_values 2 bytes.  d_dense 2 bytes; 16-byte
+ * alignment (any torch allocation) selects the fast store path.  Workspace
+ * 256 bytes.
+ *
+ * WORKSPACE.  Parallel decompression needs, for every tile of ENDOR_TILE_ELEMS
+ * consecutive flat positions, the number of 1 bits before it (the value the
+ * running counter k of Algorithm 2 has when it reaches the tile).  That table is
+ * built on the device into a caller-provided workspace of
+ * endor_workspace_bytes() bytes.  Calls that overlap in time need distinct
+ * workspaces.  The table depends only on the bitmap, so a caller that
+ * decompresses the same matrix repeatedly (every generated token, in offloaded
+ * inference) may build it once with endor_build_offsets and then call the
+ * *_with_offsets entry points.
+ */
+#ifndef ENDOR_H_
+#define ENDOR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int endor_status;
+enum {
+    ENDOR_OK = 0,
+    ENDOR_ERR_INVALID_ARG = 1,      /* NULL pointer, negative size, misaligned buffer, count out of range */
+    ENDOR_ERR_BUFFER_TOO_SMALL = 2, /* values_capacity or workspace_bytes too small */
+    ENDOR_ERR_UNSUPPORTED = 3,      /* rows*cols >= 2^34 */
+    ENDOR_ERR_HIP = 4               /* a HIP launch or API call failed */
+};
+
+/* Elements per tile of the device offset table (fixed; part of the workspace layout). */
+#define ENDOR_TILE_ELEMS 4096
+/* Most matrices one batched launch takes; endor_decompress_batch splits longer lists itself. */
+#define ENDOR_MAX_BATCH 16
+
+/* One compressed matrix and where to put its dense form.  All pointers are device pointers. */
+typedef struct endor_matrix {
+    int64_t rows;
+    int64_t cols;
+    const uint8_t *d_bitmap;  /* endor_bitmap_bytes(rows, cols) bytes */
+    const uint16_t *d_values; /* nnz elements */
+    int64_t nnz;              /* number of packed values; reads never go past it */
+    uint16_t *d_dense;        /* out: rows*cols elements, row-major, contiguous */
+} endor_matrix;
+
+/* Human-readable name of a status code.  Static storage. */
+const char *endor_status_string(endor_status s);
+
+/* Bytes of the bitmap buffer of a rows x cols matrix: 8 * ceil(rows*cols/64)
+ * (Section 4.1's rows*cols/8, rounded up to whole 64-bit words).  0 on bad sizes. */
+size_t endor_bitmap_bytes(int64_t rows, int64_t cols);
+
+/* Bytes of device workspace one matrix needs (a multiple of 256).  0 on bad sizes. */
+size_t endor_workspace_bytes(int64_t rows, int64_t cols);
+
+/* Bytes of device workspace a batch needs: the sum over its matrices.  Only rows
+ * and cols of each entry are read.  0 on bad arguments. */
+size_t endor_batch_workspace_bytes(const endor_matrix *mats, int count);
+
+/*
+ * HOST.  Algorithm 1 (Section 4.1, "Compression"): walk W in row-major order,
+ * append every non-zero element to `values` and its bit to `bitmap`.
+ *
+ *   dense            in, host: rows*cols elements, row-major, contiguous
+ *   bitmap           out, host: endor_bitmap_bytes(rows, cols) bytes, fully written
+ *   values           out, host: room for values_capacity elements; may be NULL with
+ *                    values_capacity 0 for a counting pass (bitmap, row_offsets and
+ *                    *nnz_out are still produced)
+ *   row_offsets      out, host, or NULL: rows+1 entries, row_offsets[i] = number of
+ *                    non-zeros in rows before i, row_offsets[rows] = nnz
+ *   nnz_out          out, host, or NULL: number of non-zeros
+ *
+ * ENDOR_ERR_BUFFER_TOO_SMALL if values != NULL and nnz > values_capacity; then
+ * bitmap, row_offsets and *nnz_out are valid and values is untouched.
+ * Runs on several host threads; returns when done.
+ */
+endor_status endor_compress(const uint16_t *dense, int64_t rows, int64_t cols,
+                            uint8_t *bitmap, uint16_t *values, int64_t values_capacity,
+                            int64_t *row_offsets, int64_t *nnz_out);
+
+/*
+ * DEVICE.  Build the tile offset table of one bitmap into d_workspace (the
+ * counter k of Algorithm 2 sampled every ENDOR_TILE_ELEMS positions), and, if
+ * d_row_offsets is not NULL, also the rows+1 per-row offsets
+ * (d_row_offsets[i] = number of 1 bits before flat position i*cols;
+ * d_row_offsets[rows] = total number of 1 bits, which a caller can compare with
+ * nnz to validate a blob).
+ */
+endor_status endor_build_offsets(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                 void *d_workspace, size_t workspace_bytes,
+                                 int64_t *d_row_offsets, void *stream);
+
+/*
+ * DEVICE.  Algorithm 2 (Section 4.1, "Decompression") in parallel form: every one
+ * of the rows*cols output elements is written exactly once, with the next unread
+ * value where the bit is 1 and the all-zero pattern where it is 0.  Builds the
+ * offset table into d_workspace first (same work as endor_build_offsets without
+ * row offsets), then expands.
+ */
+endor_status endor_decompress(int64_t rows, int64_t cols,
+                              const uint8_t *d_bitmap, const uint16_t *d_values, int64_t nnz,
+                              void *d_workspace, size_t workspace_bytes,
+                              uint16_t *d_dense, void *stream);
+
+/* DEVICE.  As endor_decompress, but d_workspace already holds the table that
+ * endor_build_offsets (or an earlier endor_decompress) wrote for this bitmap. */
+endor_status endor_decompress_with_offsets(int64_t rows, int64_t cols,
+                                           const uint8_t *d_bitmap, const uint16_t *d_values,
+                                           int64_t nnz,
+                                           const void *d_workspace, size_t workspace_bytes,
+                                           uint16_t *d_dense, void *stream);
+
+/*
+ * DEVICE.  Decompress `count` matrices (e.g. all linear weights of one decoder
+ * layer) with one pair of launches per ENDOR_MAX_BATCH matrices instead of one
+ * pair per matrix.  `mats` is a HOST array, read before the call returns.
+ * Matrix m uses the workspace slice that starts at the sum of
+ * endor_workspace_bytes() of the matrices before it.
+ */
+endor_status endor_decompress_batch(const endor_matrix *mats, int count,
+                                    void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* DEVICE.  Batch form of endor_build_offsets (no row offsets) and of
+ * endor_decompress_with_offsets, same workspace slicing as endor_decompress_batch. */
+endor_status endor_build_offsets_batch(const endor_matrix *mats, int count,
+                                       void *d_workspace, size_t workspace_bytes, void *stream);
+endor_status endor_decompress_batch_with_offsets(const endor_matrix *mats, int count,
+                                                 const void *d_workspace, size_t workspace_bytes,
+                                                 void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENDOR_H_ */

@@ -1,1 +1,259 @@
-"""placeholder, replaced below"""
+"""Thin ctypes binding over the C-ABI library of include/endor.h.
+
+Argument marshalling only: every step of the path (Algorithm 1 on the host,
+Algorithm 2 and its offset table on the GPU; Section 4.1) runs inside
+libendor.so.  torch is used for device memory and streams and nothing else.
+There is no fallback: if the library has not been built, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+__all__ = [
+    "EndorError", "Compressed", "DeviceMatrix", "lib", "library_path", "TILE_ELEMS", "MAX_BATCH",
+    "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
+    "build_offsets", "decompress", "decompress_with_offsets",
+    "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
+]
+
+TILE_ELEMS = 4096
+MAX_BATCH = 16
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libendor.so")
+_lib = None
+
+_i64 = ctypes.c_int64
+_p = ctypes.c_void_p
+_sz = ctypes.c_size_t
+
+
+class EndorError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        name = lib().endor_status_string(status).decode()
+        super().__init__(f"{where}: {name} (status {status})")
+
+
+class _Matrix(ctypes.Structure):
+    _fields_ = [("rows", _i64), ("cols", _i64), ("d_bitmap", _p), ("d_values", _p),
+                ("nnz", _i64), ("d_dense", _p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2406_11674_amd.build` "
+                "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.endor_status_string.restype = ctypes.c_char_p
+        L.endor_status_string.argtypes = [ctypes.c_int]
+        L.endor_bitmap_bytes.restype = _sz
+        L.endor_bitmap_bytes.argtypes = [_i64, _i64]
+        L.endor_workspace_bytes.restype = _sz
+        L.endor_workspace_bytes.argtypes = [_i64, _i64]
+        L.endor_batch_workspace_bytes.restype = _sz
+        L.endor_batch_workspace_bytes.argtypes = [_p, ctypes.c_int]
+        L.endor_compress.restype = ctypes.c_int
+        L.endor_compress.argtypes = [_p, _i64, _i64, _p, _p, _i64, _p, _p]
+        L.endor_build_offsets.restype = ctypes.c_int
+        L.endor_build_offsets.argtypes = [_i64, _i64, _p, _p, _sz, _p, _p]
+        L.endor_decompress.restype = ctypes.c_int
+        L.endor_decompress.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
+        L.endor_decompress_with_offsets.restype = ctypes.c_int
+        L.endor_decompress_with_offsets.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
+        for name in ("endor_decompress_batch", "endor_build_offsets_batch",
+                     "endor_decompress_batch_with_offsets"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise EndorError(status, where)
+
+
+def bitmap_bytes(rows: int, cols: int) -> int:
+    return int(lib().endor_bitmap_bytes(rows, cols))
+
+
+def workspace_bytes(rows: int, cols: int) -> int:
+    return int(lib().endor_workspace_bytes(rows, cols))
+
+
+# ------------------------------------------------------------------ host: compression
+
+@dataclass
+class Compressed:
+    """One matrix in the bitmap format, in host memory."""
+    rows: int
+    cols: int
+    bitmap: np.ndarray       # uint8[bitmap_bytes(rows, cols)]
+    values: np.ndarray       # uint16[nnz]
+    row_offsets: np.ndarray  # int64[rows + 1]
+
+    @property
+    def nnz(self) -> int:
+        return int(self.values.size)
+
+
+def compress(dense: np.ndarray, want_row_offsets: bool = True) -> Compressed:
+    """endor_compress on a 2-d array of 16-bit elements (float16 / int16 / uint16)."""
+    if dense.ndim != 2 or dense.dtype.itemsize != 2:
+        raise ValueError("dense must be a 2-d array of 16-bit elements")
+    W = np.ascontiguousarray(dense).view(np.uint16)
+    rows, cols = W.shape
+    L = lib()
+    bitmap = np.empty(bitmap_bytes(rows, cols), dtype=np.uint8)
+    row_offsets = np.empty(rows + 1, dtype=np.int64) if want_row_offsets else None
+    nnz = _i64(0)
+    ro = row_offsets.ctypes.data if want_row_offsets else None
+    # counting pass, then the packing pass into an exactly sized buffer
+    _check(L.endor_compress(W.ctypes.data, rows, cols, bitmap.ctypes.data, None, 0, ro,
+                            ctypes.byref(nnz)), "endor_compress(count)")
+    values = np.empty(nnz.value, dtype=np.uint16)
+    _check(L.endor_compress(W.ctypes.data, rows, cols, bitmap.ctypes.data, values.ctypes.data,
+                            values.size, ro, ctypes.byref(nnz)), "endor_compress")
+    return Compressed(rows, cols, bitmap, values, row_offsets)
+
+
+# ------------------------------------------------------------------ device side
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_handle(stream) -> int:
+    torch = _torch()
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+@dataclass
+class DeviceMatrix:
+    """One compressed matrix resident in device memory (torch tensors own the memory)."""
+    rows: int
+    cols: int
+    bitmap: object   # torch.uint8[bitmap_bytes]
+    values: object   # torch.int16[nnz]
+    nnz: int
+
+
+def to_device(c: Compressed, device="cuda") -> DeviceMatrix:
+    torch = _torch()
+    bm = torch.from_numpy(c.bitmap).to(device)
+    vals = torch.from_numpy(c.values.view(np.int16)).to(device)
+    return DeviceMatrix(c.rows, c.cols, bm, vals, c.nnz)
+
+
+def _new_workspace(nbytes: int, device):
+    torch = _torch()
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _new_dense(rows, cols, device):
+    torch = _torch()
+    return torch.empty((rows, cols), dtype=torch.int16, device=device)
+
+
+def build_offsets(m: DeviceMatrix, workspace=None, row_offsets: bool = False, stream=None):
+    """endor_build_offsets.  Returns (workspace, row_offsets tensor or None)."""
+    torch = _torch()
+    if workspace is None:
+        workspace = _new_workspace(workspace_bytes(m.rows, m.cols), m.bitmap.device)
+    ro = torch.empty(m.rows + 1, dtype=torch.int64, device=m.bitmap.device) if row_offsets else None
+    _check(lib().endor_build_offsets(m.rows, m.cols, _dptr(m.bitmap), _dptr(workspace),
+                                     workspace.numel(), _dptr(ro), _stream_handle(stream)),
+           "endor_build_offsets")
+    return workspace, ro
+
+
+def decompress(m: DeviceMatrix, out=None, workspace=None, stream=None):
+    """endor_decompress.  `out`: any 2-byte-element tensor of rows*cols elements."""
+    if out is None:
+        out = _new_dense(m.rows, m.cols, m.bitmap.device)
+    if workspace is None:
+        workspace = _new_workspace(workspace_bytes(m.rows, m.cols), m.bitmap.device)
+    _check(lib().endor_decompress(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz,
+                                  _dptr(workspace), workspace.numel(), _dptr(out),
+                                  _stream_handle(stream)), "endor_decompress")
+    return out
+
+
+def decompress_with_offsets(m: DeviceMatrix, workspace, out=None, stream=None):
+    if out is None:
+        out = _new_dense(m.rows, m.cols, m.bitmap.device)
+    _check(lib().endor_decompress_with_offsets(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values),
+                                               m.nnz, _dptr(workspace), workspace.numel(),
+                                               _dptr(out), _stream_handle(stream)),
+           "endor_decompress_with_offsets")
+    return out
+
+
+def _descs(mats, outs):
+    arr = (_Matrix * len(mats))()
+    for i, m in enumerate(mats):
+        arr[i].rows, arr[i].cols = m.rows, m.cols
+        arr[i].d_bitmap = _dptr(m.bitmap)
+        arr[i].d_values = _dptr(m.values)
+        arr[i].nnz = m.nnz
+        arr[i].d_dense = _dptr(outs[i]) if outs is not None else 0
+    return arr
+
+
+def batch_workspace_bytes(mats) -> int:
+    arr = _descs(mats, None)
+    return int(lib().endor_batch_workspace_bytes(ctypes.addressof(arr), len(mats)))
+
+
+def _batch(fn_name, mats, outs, workspace, stream):
+    arr = _descs(mats, outs)
+    _check(getattr(lib(), fn_name)(ctypes.addressof(arr), len(mats), _dptr(workspace),
+                                   0 if workspace is None else workspace.numel(),
+                                   _stream_handle(stream)), fn_name)
+
+
+def decompress_batch(mats, outs=None, workspace=None, stream=None):
+    """endor_decompress_batch over a list of DeviceMatrix.  Returns (outs, workspace)."""
+    if not mats:
+        return [], workspace
+    dev = mats[0].bitmap.device
+    if outs is None:
+        outs = [_new_dense(m.rows, m.cols, dev) for m in mats]
+    if workspace is None:
+        workspace = _new_workspace(batch_workspace_bytes(mats), dev)
+    _batch("endor_decompress_batch", mats, outs, workspace, stream)
+    return outs, workspace
+
+
+def build_offsets_batch(mats, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _new_workspace(batch_workspace_bytes(mats), mats[0].bitmap.device)
+    _batch("endor_build_offsets_batch", mats, None, workspace, stream)
+    return workspace
+
+
+def decompress_batch_with_offsets(mats, workspace, outs=None, stream=None):
+    if outs is None:
+        outs = [_new_dense(m.rows, m.cols, mats[0].bitmap.device) for m in mats]
+    _batch("endor_decompress_batch_with_offsets", mats, outs, workspace, stream)
+    return outs

@@ -1,0 +1,183 @@
+// Host side of the Endor library: size helpers, status strings and the
+// compressor (Algorithm 1 of the paper, Section 4.1 "Compression").
+//
+// The compressor is the off-line step of the method: it walks the dense matrix
+// in row-major order once and emits the position bitmap and the packed non-zero
+// values.  Here the walk is split over host threads by ranges of 64-bit bitmap
+// words: pass 1 builds the bitmap words of a range and counts its 1 bits, a
+// serial prefix over the per-range counts gives each range its start in the
+// value stream, pass 2 packs the values and samples the running count at every
+// row start.
+#include "endor.h"
+
+#include <algorithm>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#if defined(__SSE2__)
+#include <emmintrin.h>
+#endif
+
+namespace {
+
+constexpr int64_t kMaxElems = int64_t(1) << 34;
+
+bool dims_ok(int64_t rows, int64_t cols) {
+    if (rows < 0 || cols < 0) return false;
+    if (rows == 0 || cols == 0) return true;
+    return cols <= (kMaxElems - 1) / rows;  // rows*cols < 2^34, without overflow
+}
+
+// bit i of the result = (d[i] != 0), for 64 consecutive elements
+inline uint64_t nonzero_mask64(const uint16_t *d) {
+#if defined(__SSE2__)
+    const __m128i zero = _mm_setzero_si128();
+    uint64_t m = 0;
+    for (int g = 0; g < 4; ++g) {
+        __m128i a = _mm_loadu_si128(reinterpret_cast<const __m128i *>(d + 16 * g));
+        __m128i b = _mm_loadu_si128(reinterpret_cast<const __m128i *>(d + 16 * g + 8));
+        // 0xFFFF where the element is zero; narrow to bytes, one bit per byte
+        __m128i z = _mm_packs_epi16(_mm_cmpeq_epi16(a, zero), _mm_cmpeq_epi16(b, zero));
+        uint64_t zeros = static_cast<uint32_t>(_mm_movemask_epi8(z));
+        m |= ((~zeros) & 0xFFFFull) << (16 * g);
+    }
+    return m;
+#else
+    uint64_t m = 0;
+    for (int i = 0; i < 64; ++i) m |= uint64_t(d[i] != 0) << i;
+    return m;
+#endif
+}
+
+inline uint64_t nonzero_mask_tail(const uint16_t *d, int count) {
+    uint64_t m = 0;
+    for (int i = 0; i < count; ++i) m |= uint64_t(d[i] != 0) << i;
+    return m;
+}
+
+struct Range {
+    int64_t w0, w1;    // bitmap words [w0, w1)
+    int64_t ones = 0;  // 1 bits in the range
+    int64_t base = 0;  // 1 bits before the range
+};
+
+template <class F>
+void run_threads(int nthreads, F &&f) {
+    if (nthreads <= 1) {
+        f(0);
+        return;
+    }
+    std::vector<std::thread> pool;
+    pool.reserve(nthreads - 1);
+    for (int t = 1; t < nthreads; ++t) pool.emplace_back([&f, t] { f(t); });
+    f(0);
+    for (auto &th : pool) th.join();
+}
+
+}  // namespace
+
+extern "C" const char *endor_status_string(endor_status s) {
+    switch (s) {
+        case ENDOR_OK: return "ok";
+        case ENDOR_ERR_INVALID_ARG: return "invalid argument";
+        case ENDOR_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case ENDOR_ERR_UNSUPPORTED: return "unsupported size";
+        case ENDOR_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" size_t endor_bitmap_bytes(int64_t rows, int64_t cols) {
+    if (!dims_ok(rows, cols)) return 0;
+    const int64_t n = rows * cols;
+    return static_cast<size_t>((n + 63) / 64) * 8;
+}
+
+extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int64_t cols,
+                                       uint8_t *bitmap, uint16_t *values, int64_t values_capacity,
+                                       int64_t *row_offsets, int64_t *nnz_out) {
+    if (rows < 0 || cols < 0 || values_capacity < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    const int64_t n = rows * cols;
+    if (n == 0) {
+        if (row_offsets) std::fill(row_offsets, row_offsets + rows + 1, int64_t(0));
+        if (nnz_out) *nnz_out = 0;
+        return ENDOR_OK;
+    }
+    if (!dense || !bitmap) return ENDOR_ERR_INVALID_ARG;
+    if (!values && values_capacity != 0) return ENDOR_ERR_INVALID_ARG;
+
+    const int64_t nwords = (n + 63) / 64;
+    const int64_t full_words = n / 64;
+    unsigned hw = std::thread::hardware_concurrency();
+    int nthreads = static_cast<int>(std::min<int64_t>(hw ? hw : 1, std::max<int64_t>(1, nwords / 8192)));
+    nthreads = std::min(nthreads, 64);
+    std::vector<Range> ranges(nthreads);
+    for (int t = 0; t < nthreads; ++t) {
+        ranges[t].w0 = nwords * t / nthreads;
+        ranges[t].w1 = nwords * (t + 1) / nthreads;
+    }
+
+    // pass 1: bitmap words and per-range counts.  The bitmap may be only byte
+    // aligned on the host, so words are stored with memcpy.
+    run_threads(nthreads, [&](int t) {
+        Range &r = ranges[t];
+        int64_t ones = 0;
+        for (int64_t w = r.w0; w < r.w1; ++w) {
+            uint64_t m = (w < full_words) ? nonzero_mask64(dense + 64 * w)
+                                          : nonzero_mask_tail(dense + 64 * w, static_cast<int>(n - 64 * w));
+            std::memcpy(bitmap + 8 * w, &m, 8);
+            ones += __builtin_popcountll(m);
+        }
+        r.ones = ones;
+    });
+
+    int64_t nnz = 0;
+    for (auto &r : ranges) {
+        r.base = nnz;
+        nnz += r.ones;
+    }
+    if (nnz_out) *nnz_out = nnz;
+    const bool pack = values != nullptr && nnz <= values_capacity;
+
+    // pass 2: pack the values of each range at its start, and sample the running
+    // count at the row starts that fall into the range.
+    run_threads(nthreads, [&](int t) {
+        const Range &r = ranges[t];
+        int64_t k = r.base;
+        // first row whose start e = i*cols lies at or after the range's first element
+        int64_t next_row = row_offsets ? (64 * r.w0 + cols - 1) / cols : rows;
+        for (int64_t w = r.w0; w < r.w1; ++w) {
+            uint64_t m;
+            std::memcpy(&m, bitmap + 8 * w, 8);
+            const int64_t e0 = 64 * w;
+            // row starts inside this word (the entry for position rows*cols is
+            // written after the loop)
+            while (next_row < rows && next_row * cols < e0 + 64) {
+                const int bit = static_cast<int>(next_row * cols - e0);  // 0..63
+                const uint64_t below = bit ? (m & (~uint64_t(0) >> (64 - bit))) : 0;
+                row_offsets[next_row] = k + __builtin_popcountll(below);
+                ++next_row;
+            }
+            if (pack) {
+                const uint16_t *d = dense + e0;
+                if (m == ~uint64_t(0)) {
+                    std::memcpy(values + k, d, 128);
+                    k += 64;
+                } else {
+                    uint64_t mm = m;
+                    while (mm) {
+                        values[k++] = d[__builtin_ctzll(mm)];
+                        mm &= mm - 1;
+                    }
+                }
+            } else {
+                k += __builtin_popcountll(m);
+            }
+        }
+    });
+    if (row_offsets) row_offsets[rows] = nnz;
+    if (values != nullptr && nnz > values_capacity) return ENDOR_ERR_BUFFER_TOO_SMALL;
+    return ENDOR_OK;
+}

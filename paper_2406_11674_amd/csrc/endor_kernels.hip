@@ -1,0 +1,544 @@
+// Device side of the Endor library for gfx950 (MI355X): the parallel form of
+// Algorithm 2 (Section 4.1, "Decompression") and the offset table it needs.
+//
+// Algorithm 2 is a sequential walk with one running counter k: position e of the
+// flat bit vector receives values[k] when bit e is 1 (then k advances) and the
+// all-zero pattern otherwise.  Hence out[e] = bit(e) ? values[rank(e)] : 0 with
+// rank(e) = number of 1 bits before e, and the work splits into
+//
+//   1. endor_tile_offsets_kernel: rank at every tile start (a tile is 4096
+//      consecutive flat positions = 64 bitmap words = one 64-lane wave's worth of
+//      words).  One workgroup covers a chunk of 256 tiles: it popcounts the chunk's
+//      128 KiB of bitmap, scans the 256 tile counts and stores the tile offsets
+//      relative to the chunk start plus the chunk's total.
+//   2. endor_expand_kernel: one wave per tile, waves fully independent (no
+//      workgroup barrier).  The wave adds up the totals of the chunks before its
+//      own (a few loads per lane) to get the chunk's absolute start, stages the
+//      tile's contiguous slice of `values` into LDS with 16-byte loads, scans the
+//      64 word popcounts across lanes (DPP), and then, in 8 steps of 512 elements,
+//      every lane turns one bitmap byte into 8 output elements (8 LDS reads at
+//      rank-within-byte offsets, masked by the bits) and issues one 16-byte store,
+//      so a wave writes 1 KiB of contiguous dense output per store instruction.
+//
+// The path is bound by HBM traffic (2 bytes written, 1/8 + 2p bytes read per
+// element), so there is no matrix-core work here; all arithmetic is integer and
+// the values are only ever moved, never interpreted.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "endor.h"
+
+namespace {
+
+constexpr int kTileElems = ENDOR_TILE_ELEMS;  // flat positions per tile
+constexpr int kTileWords = kTileElems / 64;   // 64-bit bitmap words per tile (= lanes per wave)
+constexpr int kTilesPerChunk = 256;           // tiles one count workgroup covers
+constexpr int kChunkStride = kTilesPerChunk + 1;
+constexpr int kBlock = 256;                   // threads per workgroup, both kernels
+constexpr int kWaves = kBlock / 64;
+constexpr int kTilesPerWave = 4;              // consecutive tiles one expand wave walks
+constexpr int kTilesPerBlock = kWaves * kTilesPerWave;
+constexpr int kBlocksPerChunk = kTilesPerChunk / kTilesPerBlock;
+constexpr int kStageChunks = (2 * (7 + kTileElems + 7) + 15) / 16;  // 16-byte units of LDS value staging
+constexpr int kStageRounds = (kStageChunks + 63) / 64;
+constexpr int64_t kMaxElems = int64_t(1) << 34;
+
+static_assert(kTileWords == 64, "one bitmap word per lane");
+static_assert(kTilesPerChunk == kBlock, "one tile count per thread in the chunk scan");
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct MatParams {
+    const uint64_t *bitmap;
+    const uint16_t *values;
+    uint16_t *dense;
+    uint32_t *chunk_total;  // [nchunks] 1 bits per chunk
+    uint32_t *tile_off;     // [nchunks][257] 1 bits before each tile, relative to the chunk start
+    int64_t n;              // rows*cols
+    int64_t nnz;
+    uint32_t chunk_begin;   // first workgroup-chunk of this matrix inside the batch
+    uint32_t nchunks;
+};
+
+struct BatchParams {
+    MatParams m[ENDOR_MAX_BATCH];
+    int count;
+};
+
+// ---------------------------------------------------------------- wave primitives
+
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t x) {
+    // lanes without a source, and rows masked off, receive 0
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, kRowMask, 0xf, true));
+}
+
+// inclusive prefix sum within each row of 16 lanes (row_shr:1,2,4,8)
+__device__ __forceinline__ uint32_t row_inclusive_scan(uint32_t x) {
+    x += dpp_or_zero<0x111, 0xf>(x);
+    x += dpp_or_zero<0x112, 0xf>(x);
+    x += dpp_or_zero<0x114, 0xf>(x);
+    x += dpp_or_zero<0x118, 0xf>(x);
+    return x;
+}
+
+// inclusive prefix sum over the 64 lanes of a wave
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+    x = row_inclusive_scan(x);
+    x += dpp_or_zero<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
+    x += dpp_or_zero<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(wave_inclusive_scan(x)), 63));
+}
+
+// Bitmap word `w` of a matrix with `full_words` complete words and `tail_bits`
+// valid bits in the word after them; pad bits and words past the end read as 0.
+__device__ __forceinline__ uint64_t load_word_guarded(const uint64_t *bitmap, int64_t w,
+                                                      int64_t full_words, uint32_t tail_bits) {
+    if (w < full_words) return bitmap[w];
+    if (w == full_words && tail_bits != 0) return bitmap[w] & ((uint64_t(1) << tail_bits) - 1);
+    return 0;
+}
+
+__device__ __forceinline__ int find_matrix(const BatchParams &P, uint32_t chunk) {
+    int mi = 0;
+    for (int i = 1; i < P.count; ++i) mi = (chunk >= P.m[i].chunk_begin) ? i : mi;
+    return mi;
+}
+
+// Number of 1 bits before chunk c of the matrix: sum of the earlier chunks' totals.
+// c < 2^14 and a total is at most 2^20, so a lane's partial sum fits 32 bits; the
+// two 16-bit halves are summed across lanes separately to keep 64 bits.
+__device__ __forceinline__ uint64_t chunk_base(const uint32_t *chunk_total, uint32_t c, uint32_t lane) {
+    if (c == 0) return 0;
+    uint32_t part = 0;
+    for (uint32_t j = lane; j < c; j += 64) part += chunk_total[j];
+    const uint32_t lo = wave_sum(part & 0xffffu);
+    const uint32_t hi = wave_sum(part >> 16);
+    return uint64_t(lo) + (uint64_t(hi) << 16);
+}
+
+// ---------------------------------------------------------------- kernel 1: tile offsets
+
+struct alignas(16) WordPair {
+    uint64_t a, b;
+};
+
+__global__ __launch_bounds__(kBlock) void endor_tile_offsets_kernel(BatchParams P) {
+    __shared__ uint32_t s_cnt[kTilesPerChunk];
+    __shared__ uint32_t s_wave[kWaves];
+
+    const uint32_t gc = blockIdx.x;
+    const MatParams &M = P.m[find_matrix(P, gc)];
+    const uint32_t c = gc - M.chunk_begin;
+    const uint64_t *bitmap = M.bitmap;
+    const int64_t full_words = M.n >> 6;
+    const uint32_t tail_bits = static_cast<uint32_t>(M.n & 63);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+
+    // this wave's 64 tiles = 4096 words; one step reads 128 words (two tiles):
+    // lanes 0..31 hold tile 2i, lanes 32..63 tile 2i+1, two words per lane
+    const int64_t wbase = (int64_t(c) * kTilesPerChunk + wave * 64) * kTileWords;
+    int64_t fast = (full_words - wbase) / 128;  // steps with all 128 words complete
+    fast = fast < 0 ? 0 : (fast > 32 ? 32 : fast);
+    const bool bitmap16 = (reinterpret_cast<uintptr_t>(bitmap) & 15) == 0;
+
+    int i = 0;
+    if (bitmap16) {
+#pragma unroll 8
+        for (; i < static_cast<int>(fast); ++i) {
+            const WordPair wp = *reinterpret_cast<const WordPair *>(bitmap + wbase + i * 128 + lane * 2);
+            uint32_t p = __popcll(wp.a) + __popcll(wp.b);
+            p = row_inclusive_scan(p);
+            p += dpp_or_zero<0x142, 0xa>(p);
+            if ((lane & 31) == 31) s_cnt[wave * 64 + 2 * i + (lane >> 5)] = p;
+        }
+    }
+    for (; i < 32; ++i) {
+        const int64_t w = wbase + i * 128 + lane * 2;
+        uint32_t p = __popcll(load_word_guarded(bitmap, w, full_words, tail_bits)) +
+                     __popcll(load_word_guarded(bitmap, w + 1, full_words, tail_bits));
+        p = row_inclusive_scan(p);
+        p += dpp_or_zero<0x142, 0xa>(p);
+        if ((lane & 31) == 31) s_cnt[wave * 64 + 2 * i + (lane >> 5)] = p;
+    }
+    __syncthreads();
+
+    const uint32_t cnt = s_cnt[threadIdx.x];
+    const uint32_t incl = wave_inclusive_scan(cnt);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (uint32_t v = 0; v < wave; ++v) before += s_wave[v];
+    const uint32_t excl = before + incl - cnt;
+
+    uint32_t *to = M.tile_off + size_t(c) * kChunkStride;
+    to[threadIdx.x] = excl;
+    if (threadIdx.x == kBlock - 1) {
+        to[kTilesPerChunk] = excl + cnt;
+        M.chunk_total[c] = excl + cnt;
+    }
+}
+
+// ---------------------------------------------------------------- kernel 2: expand
+
+struct alignas(16) WaveScratch {
+    u32x4 stage[kStageChunks];   // the tile's slice of `values`, from the 16-byte boundary below it
+    uint64_t words[kTileWords];  // the tile's bitmap words
+    uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
+};
+
+// 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
+__device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
+    if (p >= vbeg && p + 16 <= vend) return *reinterpret_cast<const u32x4 *>(p);
+    uint32_t h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uintptr_t q = p + 2 * j;
+        h[j] = (q >= vbeg && q + 2 <= vend) ? *reinterpret_cast<const uint16_t *>(q) : 0u;
+    }
+    u32x4 r;
+    r.x = h[0] | (h[1] << 16);
+    r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16);
+    r.w = h[6] | (h[7] << 16);
+    return r;
+}
+
+template <bool kAlignedOut>
+__global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
+    __shared__ WaveScratch s_scratch[kWaves];
+
+    const uint32_t gc = blockIdx.x / kBlocksPerChunk;
+    const uint32_t sub = blockIdx.x % kBlocksPerChunk;
+    const MatParams &M = P.m[find_matrix(P, gc)];
+    const uint32_t c = gc - M.chunk_begin;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+
+    const int64_t n = M.n;
+    const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
+    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;  // first tile, relative to the chunk
+    const int64_t tile0 = int64_t(c) * kTilesPerChunk + tl0;
+    if (tile0 >= ntiles) return;  // whole wave; the kernel has no workgroup barrier
+
+    const uint64_t *bitmap = M.bitmap;
+    const int64_t full_words = n >> 6;
+    const uint32_t tail_bits = static_cast<uint32_t>(n & 63);
+    const uintptr_t vbeg = reinterpret_cast<uintptr_t>(M.values);
+    const uintptr_t vend = vbeg + 2 * static_cast<uintptr_t>(M.nnz);
+    const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl0;
+    const uint64_t base = chunk_base(M.chunk_total, c, lane);
+    WaveScratch &S = s_scratch[wave];
+    const uint16_t *stage16 = reinterpret_cast<const uint16_t *>(S.stage);
+
+    for (int t = 0; t < kTilesPerWave; ++t) {
+        const int64_t tile = tile0 + t;
+        if (tile >= ntiles) break;
+        const uint32_t o0 = tile_off[t];
+        uint32_t cnt = tile_off[t + 1] - o0;  // 1 bits in this tile
+        cnt = cnt > kTileElems ? kTileElems : cnt;  // a stale or foreign table must not overrun the staging area
+
+        // --- issue the loads of the tile's value slice (16-byte units from the
+        //     16-byte boundary at or below its first value)
+        const uintptr_t a = vbeg + 2 * (base + o0);
+        const uintptr_t a16 = a & ~uintptr_t(15);
+        const uint32_t shift = static_cast<uint32_t>(a - a16) >> 1;           // 0..7 elements
+        const uint32_t nch = cnt ? ((shift + cnt + 7) >> 3) : 0;              // <= kStageChunks - 1
+        u32x4 r[kStageRounds];
+#pragma unroll
+        for (int q = 0; q < kStageRounds; ++q) {
+            const uint32_t ch = q * 64 + lane;
+            if (ch < nch) r[q] = load_values16(a16 + 16 * uintptr_t(ch), vbeg, vend);
+        }
+
+        // --- bitmap word of this lane, popcount, scan across the wave
+        const uint64_t word = load_word_guarded(bitmap, tile * kTileWords + lane, full_words, tail_bits);
+        const uint32_t pc = __popcll(word);
+        const uint32_t incl = wave_inclusive_scan(pc);
+        S.words[lane] = word;
+        S.start[lane] = incl - pc + shift;
+
+#pragma unroll
+        for (int q = 0; q < kStageRounds; ++q) {
+            const uint32_t ch = q * 64 + lane;
+            if (ch < nch) S.stage[ch] = r[q];
+        }
+        // LDS operations of one wave execute in issue order, so the reads below see
+        // the writes above; the fence only keeps the compiler from moving them.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // --- expand: 8 steps of 512 elements; lane handles bitmap byte k*64+lane
+        const int64_t e0 = tile * kTileElems;
+        const bool full_tile = e0 + kTileElems <= n;
+        uint16_t *out = M.dense + e0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t wi = k * 8 + (lane >> 3);
+            const uint64_t w = S.words[wi];
+            const uint32_t sh = (lane & 7) * 8;
+            const uint32_t byte = static_cast<uint32_t>(w >> sh) & 0xffu;
+            const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
+            const uint16_t *sp = stage16 + s;
+            uint32_t h[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = sp[__popc(byte & ((1u << j) - 1))];
+            u32x4 d;
+            d.x = (h[0] | (h[1] << 16)) & (((byte & 1u) ? 0xffffu : 0u) | ((byte & 2u) ? 0xffff0000u : 0u));
+            d.y = (h[2] | (h[3] << 16)) & (((byte & 4u) ? 0xffffu : 0u) | ((byte & 8u) ? 0xffff0000u : 0u));
+            d.z = (h[4] | (h[5] << 16)) & (((byte & 16u) ? 0xffffu : 0u) | ((byte & 32u) ? 0xffff0000u : 0u));
+            d.w = (h[6] | (h[7] << 16)) & (((byte & 64u) ? 0xffffu : 0u) | ((byte & 128u) ? 0xffff0000u : 0u));
+            const uint32_t le = (k * 64 + lane) * 8;  // element index inside the tile
+            if (kAlignedOut && full_tile) {
+                __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + le));
+            } else {
+                const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (e0 + le + j < n) out[le + j] = static_cast<uint16_t>(dd[j >> 1] >> (16 * (j & 1)));
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---------------------------------------------------------------- kernel 3: row offsets
+
+// One wave per row start: rank(i*cols) = chunk start + tile offset + 1 bits of the
+// tile's words below the position.  Entry `rows` is the total number of 1 bits.
+__global__ __launch_bounds__(kBlock) void endor_row_offsets_kernel(MatParams M, int64_t rows, int64_t cols,
+                                                                   int64_t *__restrict__ row_offsets) {
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    const int64_t i = int64_t(blockIdx.x) * kWaves + wave;
+    if (i > rows) return;
+    const int64_t e = i * cols;  // == n for i == rows
+    const int64_t ntiles = (M.n + kTileElems - 1) / kTileElems;
+    int64_t tile = e >> 12;
+    uint64_t rank;
+    if (tile >= ntiles) {
+        // position n when n is a multiple of the tile size: everything counts
+        rank = chunk_base(M.chunk_total, M.nchunks, lane);
+    } else {
+        const uint32_t c = static_cast<uint32_t>(tile / kTilesPerChunk);
+        const uint32_t tl = static_cast<uint32_t>(tile % kTilesPerChunk);
+        rank = chunk_base(M.chunk_total, c, lane) + M.tile_off[size_t(c) * kChunkStride + tl];
+        const int64_t w = tile * kTileWords + lane;
+        const int64_t we = e >> 6;  // word holding position e
+        uint64_t word = 0;
+        if (w <= we) word = load_word_guarded(M.bitmap, w, M.n >> 6, static_cast<uint32_t>(M.n & 63));
+        if (w == we) word &= (uint64_t(1) << (e & 63)) - 1;
+        rank += wave_sum(__popcll(word));
+    }
+    if (lane == 0) row_offsets[i] = static_cast<int64_t>(rank);
+}
+
+// ---------------------------------------------------------------- host side
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+bool dims_ok(int64_t rows, int64_t cols) {
+    if (rows < 0 || cols < 0) return false;
+    if (rows == 0 || cols == 0) return true;
+    return cols <= (kMaxElems - 1) / rows;
+}
+
+uint32_t chunks_of(int64_t n) {
+    const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
+    return static_cast<uint32_t>((ntiles + kTilesPerChunk - 1) / kTilesPerChunk);
+}
+
+size_t workspace_bytes_n(int64_t n) {
+    const size_t nc = chunks_of(n);
+    return align256(nc * sizeof(uint32_t)) + align256(nc * kChunkStride * sizeof(uint32_t));
+}
+
+struct Group {
+    BatchParams P;
+    uint32_t chunks = 0;
+    bool aligned_out = true;
+};
+
+enum Need { kNeedBitmap = 1, kNeedValuesDense = 2 };
+
+// Validate `count` matrices starting at the workspace offset *ws_off and fill one
+// launch group.  Advances *ws_off past the slices it used.
+endor_status fill_group(const endor_matrix *mats, int count, int need, char *ws, size_t ws_bytes,
+                        size_t *ws_off, Group *g) {
+    g->P.count = 0;
+    g->chunks = 0;
+    g->aligned_out = true;
+    for (int i = 0; i < count; ++i) {
+        const endor_matrix &m = mats[i];
+        if (m.rows < 0 || m.cols < 0) return ENDOR_ERR_INVALID_ARG;
+        if (!dims_ok(m.rows, m.cols)) return ENDOR_ERR_UNSUPPORTED;
+        const int64_t n = m.rows * m.cols;
+        if (n == 0) continue;
+        if (!m.d_bitmap || (reinterpret_cast<uintptr_t>(m.d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
+        if (need & kNeedValuesDense) {
+            if (m.nnz < 0 || m.nnz > n) return ENDOR_ERR_INVALID_ARG;
+            if (!m.d_dense || (reinterpret_cast<uintptr_t>(m.d_dense) & 1)) return ENDOR_ERR_INVALID_ARG;
+            if (m.nnz > 0 && (!m.d_values || (reinterpret_cast<uintptr_t>(m.d_values) & 1)))
+                return ENDOR_ERR_INVALID_ARG;
+            if (reinterpret_cast<uintptr_t>(m.d_dense) & 15) g->aligned_out = false;
+        }
+        const uint32_t nc = chunks_of(n);
+        const size_t need_bytes = workspace_bytes_n(n);
+        if (*ws_off + need_bytes > ws_bytes) return ENDOR_ERR_BUFFER_TOO_SMALL;
+        MatParams &M = g->P.m[g->P.count++];
+        M.bitmap = reinterpret_cast<const uint64_t *>(m.d_bitmap);
+        M.values = m.d_values;
+        M.dense = m.d_dense;
+        M.chunk_total = reinterpret_cast<uint32_t *>(ws + *ws_off);
+        M.tile_off = reinterpret_cast<uint32_t *>(ws + *ws_off + align256(nc * sizeof(uint32_t)));
+        M.n = n;
+        M.nnz = m.nnz;
+        M.chunk_begin = g->chunks;
+        M.nchunks = nc;
+        g->chunks += nc;
+        *ws_off += need_bytes;
+    }
+    return ENDOR_OK;
+}
+
+endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, size_t workspace_bytes,
+                       void *stream, bool build, bool expand) {
+    if (count < 0 || (count > 0 && !mats)) return ENDOR_ERR_INVALID_ARG;
+    if (count == 0) return ENDOR_OK;
+    for (int i = 0; i < count; ++i) {
+        if (mats[i].rows < 0 || mats[i].cols < 0) return ENDOR_ERR_INVALID_ARG;
+        if (!dims_ok(mats[i].rows, mats[i].cols)) return ENDOR_ERR_UNSUPPORTED;
+    }
+    // a batch of empty matrices needs no workspace; anything else needs an aligned one
+    if (endor_batch_workspace_bytes(mats, count) != 0 &&
+        (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
+        return ENDOR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(d_workspace);
+    const int need = kNeedBitmap | (expand ? kNeedValuesDense : 0);
+
+    // validate everything before the first launch
+    {
+        size_t off = 0;
+        Group g;
+        for (int b = 0; b < count; b += ENDOR_MAX_BATCH) {
+            const int nb = count - b < ENDOR_MAX_BATCH ? count - b : ENDOR_MAX_BATCH;
+            endor_status st = fill_group(mats + b, nb, need, ws, workspace_bytes, &off, &g);
+            if (st != ENDOR_OK) return st;
+        }
+    }
+    size_t off = 0;
+    Group g;
+    for (int b = 0; b < count; b += ENDOR_MAX_BATCH) {
+        const int nb = count - b < ENDOR_MAX_BATCH ? count - b : ENDOR_MAX_BATCH;
+        fill_group(mats + b, nb, need, ws, workspace_bytes, &off, &g);
+        if (g.chunks == 0) continue;
+        if (build) {
+            hipLaunchKernelGGL(endor_tile_offsets_kernel, dim3(g.chunks), dim3(kBlock), 0, s, g.P);
+            if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+        }
+        if (expand) {
+            const dim3 grid(g.chunks * kBlocksPerChunk);
+            if (g.aligned_out)
+                hipLaunchKernelGGL(endor_expand_kernel<true>, grid, dim3(kBlock), 0, s, g.P);
+            else
+                hipLaunchKernelGGL(endor_expand_kernel<false>, grid, dim3(kBlock), 0, s, g.P);
+            if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+        }
+    }
+    return ENDOR_OK;
+}
+
+endor_matrix one_matrix(int64_t rows, int64_t cols, const uint8_t *d_bitmap, const uint16_t *d_values,
+                        int64_t nnz, uint16_t *d_dense) {
+    endor_matrix m;
+    m.rows = rows;
+    m.cols = cols;
+    m.d_bitmap = d_bitmap;
+    m.d_values = d_values;
+    m.nnz = nnz;
+    m.d_dense = d_dense;
+    return m;
+}
+
+}  // namespace
+
+extern "C" size_t endor_workspace_bytes(int64_t rows, int64_t cols) {
+    if (!dims_ok(rows, cols)) return 0;
+    return workspace_bytes_n(rows * cols);
+}
+
+extern "C" size_t endor_batch_workspace_bytes(const endor_matrix *mats, int count) {
+    if (count < 0 || (count > 0 && !mats)) return 0;
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!dims_ok(mats[i].rows, mats[i].cols)) return 0;
+        total += workspace_bytes_n(mats[i].rows * mats[i].cols);
+    }
+    return total;
+}
+
+extern "C" endor_status endor_build_offsets_batch(const endor_matrix *mats, int count, void *d_workspace,
+                                                  size_t workspace_bytes, void *stream) {
+    return run_batch(mats, count, d_workspace, workspace_bytes, stream, true, false);
+}
+
+extern "C" endor_status endor_decompress_batch(const endor_matrix *mats, int count, void *d_workspace,
+                                               size_t workspace_bytes, void *stream) {
+    return run_batch(mats, count, d_workspace, workspace_bytes, stream, true, true);
+}
+
+extern "C" endor_status endor_decompress_batch_with_offsets(const endor_matrix *mats, int count,
+                                                            const void *d_workspace, size_t workspace_bytes,
+                                                            void *stream) {
+    return run_batch(mats, count, const_cast<void *>(d_workspace), workspace_bytes, stream, false, true);
+}
+
+extern "C" endor_status endor_decompress(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                         const uint16_t *d_values, int64_t nnz, void *d_workspace,
+                                         size_t workspace_bytes, uint16_t *d_dense, void *stream) {
+    const endor_matrix m = one_matrix(rows, cols, d_bitmap, d_values, nnz, d_dense);
+    return run_batch(&m, 1, d_workspace, workspace_bytes, stream, true, true);
+}
+
+extern "C" endor_status endor_decompress_with_offsets(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                                      const uint16_t *d_values, int64_t nnz,
+                                                      const void *d_workspace, size_t workspace_bytes,
+                                                      uint16_t *d_dense, void *stream) {
+    const endor_matrix m = one_matrix(rows, cols, d_bitmap, d_values, nnz, d_dense);
+    return run_batch(&m, 1, const_cast<void *>(d_workspace), workspace_bytes, stream, false, true);
+}
+
+extern "C" endor_status endor_build_offsets(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                            void *d_workspace, size_t workspace_bytes,
+                                            int64_t *d_row_offsets, void *stream) {
+    const endor_matrix m = one_matrix(rows, cols, d_bitmap, nullptr, 0, nullptr);
+    if (d_row_offsets && (reinterpret_cast<uintptr_t>(d_row_offsets) & 7)) return ENDOR_ERR_INVALID_ARG;
+    endor_status st = run_batch(&m, 1, d_workspace, workspace_bytes, stream, true, false);
+    if (st != ENDOR_OK || !d_row_offsets) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t n = rows * cols;
+    MatParams M{};
+    if (n > 0) {
+        size_t off = 0;
+        Group g;
+        fill_group(&m, 1, kNeedBitmap, static_cast<char *>(d_workspace), workspace_bytes, &off, &g);
+        M = g.P.m[0];
+    }
+    // n == 0: nchunks == 0 and every position is >= ntiles, so all entries are 0
+    const int64_t entries = rows + 1;
+    if ((entries + kWaves - 1) / kWaves > 0x7fffffff) return ENDOR_ERR_UNSUPPORTED;
+    const unsigned blocks = static_cast<unsigned>((entries + kWaves - 1) / kWaves);
+    hipLaunchKernelGGL(endor_row_offsets_kernel, dim3(blocks), dim3(kBlock), 0, s, M, rows, cols, d_row_offsets);
+    if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    return ENDOR_OK;
+}

@@ -1,0 +1,73 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/endor.h
+declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2406_11674_amd as endor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "endor.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(endor_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared_functions()
+    assert "endor_compress" in names and "endor_decompress" in names and len(names) >= 10
+    L = endor.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_size_helpers():
+    assert endor.bitmap_bytes(9216, 36864) == 42_467_328          # Section 4.1's bitmap size
+    assert endor.bitmap_bytes(3, 5) == 8 and endor.bitmap_bytes(0, 7) == 0
+    assert endor.bitmap_bytes(-1, 5) == 0
+    assert endor.workspace_bytes(1, 1) % 256 == 0 and endor.workspace_bytes(1, 1) > 0
+    assert endor.workspace_bytes(0, 5) == 0
+    n_tiles = 8192 * 28672 // 4096
+    assert endor.workspace_bytes(8192, 28672) < 5 * n_tiles      # about one word per tile
+    assert endor.workspace_bytes(1 << 20, 1 << 20) == 0          # >= 2^34 elements
+
+
+def test_device_entry_points_reject_bad_arguments_without_launching():
+    L = endor.lib()
+    ws = 1 << 20
+    fake = 0x1000  # never dereferenced: every call below fails validation first
+    # NULL bitmap
+    assert L.endor_decompress(4, 64, None, fake, 10, fake, ws, fake, None) == 1
+    # misaligned bitmap / workspace / dense
+    assert L.endor_decompress(4, 64, fake + 4, fake, 10, fake, ws, fake, None) == 1
+    assert L.endor_decompress(4, 64, fake, fake, 10, fake + 8, ws, fake, None) == 1
+    assert L.endor_decompress(4, 64, fake, fake, 10, fake, ws, fake + 1, None) == 1
+    # nnz out of range, NULL values with nnz > 0, NULL dense
+    assert L.endor_decompress(4, 64, fake, fake, 4 * 64 + 1, fake, ws, fake, None) == 1
+    assert L.endor_decompress(4, 64, fake, None, 10, fake, ws, fake, None) == 1
+    assert L.endor_decompress(4, 64, fake, fake, 10, fake, ws, None, None) == 1
+    # workspace too small / missing
+    assert L.endor_decompress(4, 64, fake, fake, 10, fake, 16, fake, None) == 2
+    assert L.endor_decompress(4, 64, fake, fake, 10, None, 0, fake, None) == 1
+    # negative and oversized dims
+    assert L.endor_decompress(-4, 64, fake, fake, 10, fake, ws, fake, None) == 1
+    assert L.endor_decompress(1 << 20, 1 << 20, fake, fake, 10, fake, ws, fake, None) == 3
+    assert L.endor_build_offsets(4, 64, None, fake, ws, None, None) == 1
+    assert L.endor_build_offsets(4, 64, fake, fake, ws, fake + 4, None) == 1
+    assert L.endor_decompress_batch(None, 2, fake, ws, None) == 1
+    assert L.endor_decompress_batch(None, -1, fake, ws, None) == 1
+    # empty work is accepted and launches nothing
+    assert L.endor_decompress(0, 64, None, None, 0, None, 0, None, None) == 0
+    assert L.endor_decompress_batch(None, 0, None, 0, None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2406_11674_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libendor.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lib()

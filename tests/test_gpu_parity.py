@@ -1,0 +1,236 @@
+"""GPU parity: the HIP decompression path (through the C ABI) against the CPU
+oracle, element by element and bit for bit, on the same seeded host buffers.
+
+Integer / byte work throughout, so the bar is exact equality.
+"""
+import numpy as np
+import pytest
+
+import paper_2406_11674_amd as endor
+from oracle import endor_oracle as orc
+from paper_2406_11674_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+POISON = 0x7FFF  # int16 view of 0x7FFF; never produced by zero fill
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _random_compressed(rows, cols, keep, seed, zero_values=True):
+    """A compressed matrix built directly in the compressed domain: random bits,
+    arbitrary 16-bit patterns as values (the zero pattern included)."""
+    n = rows * cols
+    g = np.random.default_rng(seed)
+    bits = g.random(n) < keep
+    bitmap = np.zeros(endor.bitmap_bytes(rows, cols), np.uint8)
+    packed = np.packbits(bits, bitorder="little")
+    bitmap[: packed.size] = packed
+    values = g.integers(0, 1 << 16, size=int(bits.sum()), dtype=np.uint32).astype(np.uint16)
+    if zero_values and values.size:
+        values[:: 7] = 0
+    return endor.Compressed(rows, cols, bitmap, values, None)
+
+
+def _gpu_decompress(c, poison=True):
+    m = endor.to_device(c)
+    out = torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint16)
+
+
+SHAPES = [
+    (1, 1), (1, 7), (1, 8), (1, 9), (3, 5), (1, 63), (1, 64), (1, 65), (1, 511), (1, 512), (1, 513),
+    (1, 4095), (1, 4096), (1, 4097), (2, 4096), (3, 4097), (7, 9001),
+    (16, 4096), (17, 4095),                      # one workgroup's 16 tiles, ragged neighbour
+    (255, 4096), (256, 4096), (257, 4096),       # around one 256-tile chunk
+    (1031, 2053),                                # > 2 chunks, nothing aligned
+    (1024, 1024),                                # config 1 shape
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.1, 0.5, 0.9, 1.0])
+def test_decompress_matches_oracle(shape, keep):
+    rows, cols = shape
+    _say(f"case shape={shape} keep={keep}")
+    c = _random_compressed(rows, cols, keep, seed=rows * 31 + cols)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    got = _gpu_decompress(c)
+    assert np.array_equal(got, expect)
+
+
+def test_pad_bits_are_ignored():
+    rows, cols = 3, 1365  # N = 4095: one pad bit in the last byte, 7 more bytes of pad in the word
+    c = _random_compressed(rows, cols, 0.5, seed=2)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    c.bitmap[rows * cols // 8] |= 0x80
+    c.bitmap[rows * cols // 8 + 1:] = 0xFF
+    got = _gpu_decompress(c)
+    assert np.array_equal(got, expect)
+
+
+def test_output_is_fully_overwritten_and_nothing_else():
+    rows, cols = 37, 4099
+    n = rows * cols
+    c = _random_compressed(rows, cols, 0.5, seed=3)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values).reshape(-1)
+    m = endor.to_device(c)
+    guard = 4096
+    buf = torch.full((guard + n + guard,), POISON, dtype=torch.int16, device="cuda")
+    out = buf[guard:guard + n]                      # 16-byte aligned (guard*2 bytes)
+    for _ in range(2):                              # twice into the same buffer
+        endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint16)
+    assert np.all(host[:guard] == POISON) and np.all(host[guard + n:] == POISON)
+    assert np.array_equal(host[guard:guard + n], expect)
+
+
+@pytest.mark.parametrize("voff", [1, 3, 7])
+@pytest.mark.parametrize("ooff", [0, 1, 4])
+def test_unaligned_values_and_output(voff, ooff):
+    """values only 2-byte aligned, dense output only 2-/8-byte aligned."""
+    rows, cols = 9, 5000
+    n = rows * cols
+    c = _random_compressed(rows, cols, 0.5, seed=voff * 10 + ooff)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values).reshape(-1)
+    bm = torch.from_numpy(c.bitmap).cuda()
+    vbuf = torch.full((voff + c.nnz + 9,), 0x5555, dtype=torch.int16, device="cuda")
+    vbuf[voff:voff + c.nnz] = torch.from_numpy(c.values.view(np.int16)).cuda()
+    m = endor.DeviceMatrix(rows, cols, bm, vbuf[voff:voff + c.nnz], c.nnz)
+    obuf = torch.full((ooff + n + 16,), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress(m, out=obuf[ooff:ooff + n])
+    torch.cuda.synchronize()
+    host = obuf.cpu().numpy().view(np.uint16)
+    assert np.array_equal(host[ooff:ooff + n], expect)
+    assert np.all(host[:ooff] == POISON) and np.all(host[ooff + n:] == POISON)
+
+
+def test_bitmap_only_8_byte_aligned():
+    rows, cols = 300, 4096
+    c = _random_compressed(rows, cols, 0.5, seed=8)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    buf = torch.zeros(8 + c.bitmap.size, dtype=torch.uint8, device="cuda")
+    buf[8:] = torch.from_numpy(c.bitmap).cuda()
+    m = endor.DeviceMatrix(rows, cols, buf[8:], torch.from_numpy(c.values.view(np.int16)).cuda(), c.nnz)
+    out = endor.decompress(m)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), expect)
+
+
+def test_row_offsets_and_reuse_of_the_table():
+    rows, cols = 523, 4111
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=11, row_skew=True)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    ws, ro = endor.build_offsets(m, row_offsets=True)
+    out = endor.decompress_with_offsets(m, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(ro.cpu().numpy(), orc.row_offsets(rows, cols, c.bitmap))
+    assert np.array_equal(ro.cpu().numpy(), c.row_offsets)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, c.values))
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), w)
+
+
+def test_row_offsets_tile_aligned_total():
+    rows, cols = 64, 4096   # position rows*cols is a tile boundary
+    c = _random_compressed(rows, cols, 0.3, seed=12)
+    m = endor.to_device(c)
+    _, ro = endor.build_offsets(m, row_offsets=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(ro.cpu().numpy(), orc.row_offsets(rows, cols, c.bitmap))
+
+
+def test_empty_matrices():
+    for rows, cols in [(0, 5), (5, 0), (0, 0)]:
+        c = endor.Compressed(rows, cols, np.zeros(0, np.uint8), np.zeros(0, np.uint16), None)
+        m = endor.to_device(c)
+        out = endor.decompress(m)
+        torch.cuda.synchronize()
+        assert out.numel() == 0
+        _, ro = endor.build_offsets(m, row_offsets=True)
+        torch.cuda.synchronize()
+        assert not ro.cpu().numpy().any()
+
+
+def test_batch_of_mixed_shapes_matches_oracle():
+    shapes = [(1, 1), (64, 4096), (0, 9), (300, 4099), (17, 33), (1031, 2053)] + [(5, 777)] * 14
+    cs = [_random_compressed(r, c, 0.5, seed=100 + i) for i, (r, c) in enumerate(shapes)]
+    assert len(cs) > endor.MAX_BATCH                       # exercises the split into launch groups
+    mats = [endor.to_device(c) for c in cs]
+    outs = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in cs]
+    endor.decompress_batch(mats, outs=outs)
+    torch.cuda.synchronize()
+    for c, o in zip(cs, outs):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), orc.decompress(c.rows, c.cols, c.bitmap, c.values))
+    # table reuse in batch form
+    ws = endor.build_offsets_batch(mats)
+    outs2 = endor.decompress_batch_with_offsets(mats, ws)
+    torch.cuda.synchronize()
+    for a, b in zip(outs, outs2):
+        assert torch.equal(a, b)
+
+
+def test_round_trip_special_patterns_through_host_compress():
+    w = synth.pruned_fp16(300, 5001, 0.5, seed=21)
+    g = np.random.default_rng(1)
+    idx = g.integers(0, w.size, size=5000)
+    w.reshape(-1)[idx] = np.array([0x8000, 0x0001, 0x7C00, 0xFC00, 0x7E01, 0xFFFF], np.uint16)[g.integers(0, 6, 5000)]
+    c = endor.compress(w)
+    assert np.array_equal(_gpu_decompress(c), w)
+
+
+# ---------------------------------------------------------------------------
+# the benchmark configurations at full size, in the batched launch bench.py times
+# ---------------------------------------------------------------------------
+def _full_config(config, keep=0.5, row_skew=False, variant=0):
+    shapes = synth.CONFIGS[config]
+    cs, dense = [], []
+    for i, (name, rows, cols) in enumerate(shapes):
+        _say(f"  generating {name} {rows}x{cols} keep={keep} skew={row_skew}")
+        w = synth.pruned_fp16(rows, cols, keep, seed=synth.seed_for(config, i, variant), row_skew=row_skew)
+        cs.append(endor.compress(w, want_row_offsets=False))
+        dense.append(w)
+    return cs, dense
+
+
+def _check_full(cs, dense):
+    mats = [endor.to_device(c) for c in cs]
+    outs = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in cs]
+    endor.decompress_batch(mats, outs=outs)
+    torch.cuda.synchronize()
+    for c, w, o in zip(cs, dense, outs):
+        _say(f"  oracle {c.rows}x{c.cols}")
+        expect = orc.decompress(c.rows, c.cols, c.bitmap, c.values)     # Algorithm 2 on the CPU
+        assert np.array_equal(expect, w)                                # and the round trip is lossless
+        got = o.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, expect)
+        # size law of Section 4.1 on the real buffers
+        assert c.bitmap.nbytes + c.values.nbytes == (c.rows * c.cols) // 8 + 2 * c.nnz
+
+
+@pytest.mark.parametrize("config", [0, 1, 2, 3], ids=["1024sq", "opt66b_attn", "opt66b_ffn", "llama2_70b_layer"])
+def test_full_size_configs(config):
+    _say(f"full-size config {config}")
+    cs, dense = _full_config(config)
+    _check_full(cs, dense)
+
+
+@pytest.mark.parametrize("keep", [0.1, 0.3, 0.7])
+def test_down_proj_keep_sweep(keep):
+    _say(f"down_proj keep={keep}")
+    cs, dense = _full_config(4, keep=keep, variant=int(keep * 10))
+    assert abs(cs[0].nnz / (8192 * 28672) - keep) < 1e-3
+    _check_full(cs, dense)
+
+
+def test_down_proj_row_skew():
+    _say("down_proj Beta(2,2) row skew")
+    cs, dense = _full_config(4, row_skew=True, variant=9)
+    _check_full(cs, dense)

@@ -1,0 +1,86 @@
+"""endor_compress (host side of the C ABI; Algorithm 1, Section 4.1) against the CPU oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import paper_2406_11674_amd as endor
+from oracle import endor_oracle as orc
+from paper_2406_11674_amd import synth
+
+SHAPES = [(1, 1), (1, 63), (1, 64), (1, 65), (3, 5), (7, 13), (64, 64), (33, 65), (129, 257),
+          (5, 4095), (5, 4096), (5, 4097), (1, 100003), (1000, 1000)]
+
+
+def _dense(rows, cols, keep, seed):
+    g = np.random.default_rng(seed)
+    w = g.integers(1, 1 << 16, size=(rows, cols), dtype=np.uint32).astype(np.uint16)
+    w[g.random((rows, cols)) >= keep] = 0
+    return w
+
+
+def _oracle_bitmap_padded(rows, cols, b):
+    out = np.zeros(endor.bitmap_bytes(rows, cols), np.uint8)
+    out[: b.size] = b
+    return out
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.5, 1.0])
+def test_compress_matches_oracle(shape, keep):
+    rows, cols = shape
+    w = _dense(rows, cols, keep, seed=rows * 7 + cols)
+    c = endor.compress(w)
+    b, v, r = orc.compress(w)
+    assert c.bitmap.size == 8 * ((rows * cols + 63) // 64)
+    assert np.array_equal(c.bitmap, _oracle_bitmap_padded(rows, cols, b))   # pad bits are zero
+    assert np.array_equal(c.values, v)
+    assert np.array_equal(c.row_offsets, r)
+
+
+def test_compress_multithreaded_size_matches_oracle():
+    # large enough for several host threads (ranges of bitmap words), ragged everywhere
+    rows, cols = 1531, 4099
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=5)
+    c = endor.compress(w)
+    b, v, r = orc.compress(w)
+    assert np.array_equal(c.bitmap, _oracle_bitmap_padded(rows, cols, b))
+    assert np.array_equal(c.values, v)
+    assert np.array_equal(c.row_offsets, r)
+    assert np.array_equal(orc.decompress(rows, cols, c.bitmap, c.values), w)
+
+
+def test_compress_keeps_special_patterns():
+    w = np.array([[0x8000, 0x0001, 0, 0x7C00, 0x7E01, 0, 0xFFFF, 0]], np.uint16)
+    c = endor.compress(w)
+    assert c.values.tolist() == [0x8000, 0x0001, 0x7C00, 0x7E01, 0xFFFF]
+    assert c.bitmap[0] == 0b01011011
+
+
+def test_compress_float16_input():
+    w = np.array([[0.0, 1.5, -0.0, 2.0]], np.float16)
+    c = endor.compress(w)
+    assert c.values.view(np.float16).tolist()[0] == 1.5 and c.nnz == 3   # -0.0 is a non-zero pattern
+
+
+def test_compress_error_paths():
+    L = endor.lib()
+    w = _dense(4, 64, 0.5, 1)
+    nnz_true = int(np.count_nonzero(w))
+    bm = np.zeros(endor.bitmap_bytes(4, 64), np.uint8)
+    vals = np.full(nnz_true, 0xEEEE, np.uint16)
+    nnz = ctypes.c_int64(-1)
+    call = L.endor_compress
+    assert call(w.ctypes.data, -1, 64, bm.ctypes.data, None, 0, None, None) == 1
+    assert call(None, 4, 64, bm.ctypes.data, None, 0, None, None) == 1
+    assert call(w.ctypes.data, 4, 64, None, None, 0, None, None) == 1
+    assert call(w.ctypes.data, 4, 64, bm.ctypes.data, None, 5, None, None) == 1
+    assert call(w.ctypes.data, 1 << 20, 1 << 20, bm.ctypes.data, None, 0, None, None) == 3
+    # capacity one short: status 2, nnz reported, values untouched
+    st = call(w.ctypes.data, 4, 64, bm.ctypes.data, vals.ctypes.data, nnz_true - 1, None, ctypes.byref(nnz))
+    assert st == 2 and nnz.value == nnz_true and np.all(vals == 0xEEEE)
+    # empty matrices are fine
+    ro = np.full(5, -1, np.int64)
+    assert call(None, 4, 0, None, None, 0, ro.ctypes.data, ctypes.byref(nnz)) == 0
+    assert nnz.value == 0 and not ro.any()
+    assert L.endor_status_string(2) == b"buffer too small"
