@@ -35,10 +35,34 @@ constexpr int kTileElems = ENDOR_TILE_ELEMS;  // flat positions per tile
 constexpr int kTileWords = kTileElems / 64;   // 64-bit bitmap words per tile (= lanes per wave)
 constexpr int kTilesPerChunk = 256;           // tiles one count workgroup covers
 constexpr int kChunkStride = kTilesPerChunk + 1;
-constexpr int kBlock = 256;                   // threads per workgroup, both kernels
+constexpr int kBlock = 256;                   // threads per workgroup of the offset kernels
 constexpr int kWaves = kBlock / 64;
-constexpr int kTilesPerWave = 4;              // consecutive tiles one expand wave walks
-constexpr int kTilesPerBlock = kWaves * kTilesPerWave;
+// expand kernel launch shape (tunable at build time)
+#ifndef ENDOR_EXPAND_WAVES
+#define ENDOR_EXPAND_WAVES 1
+#endif
+#ifndef ENDOR_TILES_PER_WAVE
+#define ENDOR_TILES_PER_WAVE 1
+#endif
+#ifndef ENDOR_NT_LOAD
+#define ENDOR_NT_LOAD 1  // 1: values are read once, stream them; the bitmap is read twice and stays cacheable
+#endif
+#ifndef ENDOR_INTERLEAVE
+#define ENDOR_INTERLEAVE 0
+#endif
+#ifndef ENDOR_NT_STORE
+#define ENDOR_NT_STORE 1
+#endif
+#ifndef ENDOR_XCD_REMAP
+#define ENDOR_XCD_REMAP 0
+#endif
+#ifndef ENDOR_LDS_PAD
+#define ENDOR_LDS_PAD 0
+#endif
+constexpr int kExpandWaves = ENDOR_EXPAND_WAVES;   // waves per expand workgroup
+constexpr int kExpandBlock = 64 * kExpandWaves;
+constexpr int kTilesPerWave = ENDOR_TILES_PER_WAVE;  // tiles one expand wave walks
+constexpr int kTilesPerBlock = kExpandWaves * kTilesPerWave;
 constexpr int kBlocksPerChunk = kTilesPerChunk / kTilesPerBlock;
 constexpr int kStageChunks = (2 * (7 + kTileElems + 7) + 15) / 16;  // 16-byte units of LDS value staging
 constexpr int kStageRounds = (kStageChunks + 63) / 64;
@@ -46,6 +70,7 @@ constexpr int64_t kMaxElems = int64_t(1) << 34;
 
 static_assert(kTileWords == 64, "one bitmap word per lane");
 static_assert(kTilesPerChunk == kBlock, "one tile count per thread in the chunk scan");
+static_assert(kTilesPerChunk % kTilesPerBlock == 0, "expand workgroups do not straddle chunks");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -64,6 +89,7 @@ struct MatParams {
 struct BatchParams {
     MatParams m[ENDOR_MAX_BATCH];
     int count;
+    uint32_t total_blocks;  // expand workgroups that have work
 };
 
 // ---------------------------------------------------------------- wave primitives
@@ -97,9 +123,10 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
 
 // Bitmap word `w` of a matrix with `full_words` complete words and `tail_bits`
 // valid bits in the word after them; pad bits and words past the end read as 0.
+template <bool kStream = false>
 __device__ __forceinline__ uint64_t load_word_guarded(const uint64_t *bitmap, int64_t w,
                                                       int64_t full_words, uint32_t tail_bits) {
-    if (w < full_words) return bitmap[w];
+    if (w < full_words) return kStream ? __builtin_nontemporal_load(bitmap + w) : bitmap[w];
     if (w == full_words && tail_bits != 0) return bitmap[w] & ((uint64_t(1) << tail_bits) - 1);
     return 0;
 }
@@ -152,8 +179,14 @@ __global__ __launch_bounds__(kBlock) void endor_tile_offsets_kernel(BatchParams 
     if (bitmap16) {
 #pragma unroll 8
         for (; i < static_cast<int>(fast); ++i) {
+#if ENDOR_NT_LOAD >= 3
+            const u32x4 wq = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(bitmap + wbase + i * 128 + lane * 2));
+            uint32_t p = __popc(wq.x) + __popc(wq.y) + __popc(wq.z) + __popc(wq.w);
+#else
             const WordPair wp = *reinterpret_cast<const WordPair *>(bitmap + wbase + i * 128 + lane * 2);
             uint32_t p = __popcll(wp.a) + __popcll(wp.b);
+#endif
             p = row_inclusive_scan(p);
             p += dpp_or_zero<0x142, 0xa>(p);
             if ((lane & 31) == 31) s_cnt[wave * 64 + 2 * i + (lane >> 5)] = p;
@@ -195,7 +228,11 @@ struct alignas(16) WaveScratch {
 
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
 __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
+#if ENDOR_NT_LOAD
+    if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+#else
     if (p >= vbeg && p + 16 <= vend) return *reinterpret_cast<const u32x4 *>(p);
+#endif
     uint32_t h[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -211,11 +248,22 @@ __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uint
 }
 
 template <bool kAlignedOut>
-__global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
-    __shared__ WaveScratch s_scratch[kWaves];
-
-    const uint32_t gc = blockIdx.x / kBlocksPerChunk;
-    const uint32_t sub = blockIdx.x % kBlocksPerChunk;
+__global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams P) {
+    __shared__ WaveScratch s_scratch[kExpandWaves];
+#if ENDOR_LDS_PAD
+    __shared__ uint32_t s_pad[ENDOR_LDS_PAD / 4];
+    if (P.count < 0) s_pad[threadIdx.x] = 1;  // never true; keeps the padding allocated
+#endif
+#if ENDOR_XCD_REMAP
+    // workgroups are handed to the 8 XCDs round-robin; give each XCD one contiguous range
+    const uint32_t per_xcd = gridDim.x / 8;
+    const uint32_t bid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (bid >= P.total_blocks) return;
+#else
+    const uint32_t bid = blockIdx.x;
+#endif
+    const uint32_t gc = bid / kBlocksPerChunk;
+    const uint32_t sub = bid % kBlocksPerChunk;
     const MatParams &M = P.m[find_matrix(P, gc)];
     const uint32_t c = gc - M.chunk_begin;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -223,7 +271,14 @@ __global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
 
     const int64_t n = M.n;
     const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
-    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;  // first tile, relative to the chunk
+    // first tile of this wave, relative to the chunk, and the step to its next one
+#if ENDOR_INTERLEAVE
+    const uint32_t tl0 = sub * kTilesPerBlock + wave;
+    constexpr int kTileStep = kExpandWaves;
+#else
+    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;
+    constexpr int kTileStep = 1;
+#endif
     const int64_t tile0 = int64_t(c) * kTilesPerChunk + tl0;
     if (tile0 >= ntiles) return;  // whole wave; the kernel has no workgroup barrier
 
@@ -238,10 +293,10 @@ __global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
     const uint16_t *stage16 = reinterpret_cast<const uint16_t *>(S.stage);
 
     for (int t = 0; t < kTilesPerWave; ++t) {
-        const int64_t tile = tile0 + t;
+        const int64_t tile = tile0 + t * kTileStep;
         if (tile >= ntiles) break;
-        const uint32_t o0 = tile_off[t];
-        uint32_t cnt = tile_off[t + 1] - o0;  // 1 bits in this tile
+        const uint32_t o0 = tile_off[t * kTileStep];
+        uint32_t cnt = tile_off[t * kTileStep + 1] - o0;  // 1 bits in this tile
         cnt = cnt > kTileElems ? kTileElems : cnt;  // a stale or foreign table must not overrun the staging area
 
         // --- issue the loads of the tile's value slice (16-byte units from the
@@ -258,7 +313,8 @@ __global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
         }
 
         // --- bitmap word of this lane, popcount, scan across the wave
-        const uint64_t word = load_word_guarded(bitmap, tile * kTileWords + lane, full_words, tail_bits);
+        const uint64_t word =
+            load_word_guarded<(ENDOR_NT_LOAD >= 2)>(bitmap, tile * kTileWords + lane, full_words, tail_bits);
         const uint32_t pc = __popcll(word);
         const uint32_t incl = wave_inclusive_scan(pc);
         S.words[lane] = word;
@@ -297,7 +353,11 @@ __global__ __launch_bounds__(kBlock) void endor_expand_kernel(BatchParams P) {
             d.w = (h[6] | (h[7] << 16)) & (((byte & 64u) ? 0xffffu : 0u) | ((byte & 128u) ? 0xffff0000u : 0u));
             const uint32_t le = (k * 64 + lane) * 8;  // element index inside the tile
             if (kAlignedOut && full_tile) {
+#if ENDOR_NT_STORE
                 __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + le));
+#else
+                *reinterpret_cast<u32x4 *>(out + le) = d;
+#endif
             } else {
                 const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
@@ -447,11 +507,16 @@ endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, s
             if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
         }
         if (expand) {
-            const dim3 grid(g.chunks * kBlocksPerChunk);
+            g.P.total_blocks = g.chunks * kBlocksPerChunk;
+#if ENDOR_XCD_REMAP
+            const dim3 grid((g.P.total_blocks + 7) / 8 * 8);
+#else
+            const dim3 grid(g.P.total_blocks);
+#endif
             if (g.aligned_out)
-                hipLaunchKernelGGL(endor_expand_kernel<true>, grid, dim3(kBlock), 0, s, g.P);
+                hipLaunchKernelGGL(endor_expand_kernel<true>, grid, dim3(kExpandBlock), 0, s, g.P);
             else
-                hipLaunchKernelGGL(endor_expand_kernel<false>, grid, dim3(kBlock), 0, s, g.P);
+                hipLaunchKernelGGL(endor_expand_kernel<false>, grid, dim3(kExpandBlock), 0, s, g.P);
             if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
         }
     }
