@@ -34,6 +34,77 @@ WORKLOADS = {
 }
 
 
+def overlap_leg(endor, torch, host, outs, args):
+    """Pinned host -> device copy of the compressed blobs, alone and overlapped with
+    decompression (two streams, double-buffered staging).  PCIe-bound by design: these
+    figures are reported beside `value`, never as it."""
+    pinned = [endor.pin(c) for c in host]
+    whole = [endor.HostBlob(c.rows, c.cols, p[0], p[1], c.nnz) for c, p in zip(host, pinned)]
+    blocks, block_outs = [], []
+    for c, p, o in zip(host, pinned, outs):
+        for b in endor.row_blocks(c, p, args.overlap_blocks):
+            blocks.append(b)
+            block_outs.append(o[b.row_begin:b.row_begin + b.rows])
+    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    compressed_bytes = sum(c.bitmap.nbytes + c.values.nbytes for c in host)
+    dense_bytes = sum(2 * c.rows * c.cols for c in host)
+
+    def buffers(blobs):
+        sb = max(endor.stage_bytes(b.rows, b.cols, b.nnz) for b in blobs)
+        wb = max(256, max(endor.workspace_bytes(b.rows, b.cols) for b in blobs))
+        return ([torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(2)],
+                [torch.empty(wb, dtype=torch.uint8, device="cuda") for _ in range(2)])
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps * 1e3
+
+    st_w, ws_w = buffers(whole)
+    st_b, ws_b = buffers(blocks)
+    dev_bm = [torch.empty(c.bitmap.size, dtype=torch.uint8, device="cuda") for c in host]
+    dev_v = [torch.empty(c.values.size, dtype=torch.int16, device="cuda") for c in host]
+
+    def copy_only():
+        with torch.cuda.stream(s_copy):
+            for (pb, pv), db, dv in zip(pinned, dev_bm, dev_v):
+                db.copy_(pb, non_blocking=True)
+                dv.copy_(pv, non_blocking=True)
+
+    def dense_copy():   # what the uncompressed baseline would move over the same link
+        with torch.cuda.stream(s_copy):
+            for o, hp in zip(outs, dense_pinned):
+                o.copy_(hp, non_blocking=True)
+
+    dense_pinned = [torch.empty((c.rows, c.cols), dtype=torch.int16, pin_memory=True) for c in host]
+    mats = [endor.DeviceMatrix(c.rows, c.cols, db, dv, c.nnz) for c, db, dv in zip(host, dev_bm, dev_v)]
+    ws = torch.empty(max(256, endor.batch_workspace_bytes(mats)), dtype=torch.uint8, device="cuda")
+    copy_only()
+    torch.cuda.synchronize()
+    ms_copy = timed(copy_only)
+    ms_dense_copy = timed(dense_copy)
+    ms_dec = timed(lambda: endor.decompress_batch(mats, outs=outs, workspace=ws, stream=s_comp), reps=20)
+    ms_pipe_whole = timed(lambda: endor.h2d_decompress_pipeline(whole, outs, st_w, ws_w, s_copy, s_comp))
+    ms_pipe_blocks = timed(lambda: endor.h2d_decompress_pipeline(blocks, block_outs, st_b, ws_b, s_copy, s_comp))
+    return {
+        "compressed_bytes": compressed_bytes, "dense_bytes": dense_bytes,
+        "ms_decompress_alone": round(ms_dec, 3),
+        "ms_h2d_copy_compressed_alone": round(ms_copy, 3),
+        "ms_h2d_copy_dense_alone": round(ms_dense_copy, 3),
+        "h2d_GBps": round(compressed_bytes / ms_copy / 1e6, 1),
+        "ms_pipeline_whole_matrices": round(ms_pipe_whole, 3),
+        "ms_pipeline_row_blocks": round(ms_pipe_blocks, 3),
+        "row_blocks_per_matrix": args.overlap_blocks,
+        "sum_copy_plus_decompress_ms": round(ms_copy + ms_dec, 3),
+        "dense_GBps_pcie_inclusive": round(dense_bytes / ms_pipe_blocks / 1e6, 1),
+        "speedup_vs_dense_copy": round(ms_dense_copy / ms_pipe_blocks, 3),
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +118,10 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=3,
                     help="number of distinct device copies of the compressed input that the timed steps "
                          "cycle through, so that no step finds its input in a cache left by the one before")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also time the pinned host-to-device copy, alone and pipelined with decompression "
+                         "on a second stream (adds an \"overlap\" object)")
+    ap.add_argument("--overlap-blocks", type=int, default=4, help="row blocks per matrix in the pipeline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (a reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -196,6 +271,9 @@ def main() -> int:
             "min_single_launch_ms": round(per[0], 4),
         },
     }
+
+    if args.overlap:
+        result["overlap"] = overlap_leg(endor, torch, host, outs, args)
 
     if not args.no_cpu_baseline:
         from oracle import endor_oracle as orc

@@ -163,6 +163,50 @@ endor_status endor_decompress_batch_with_offsets(const endor_matrix *mats, int c
                                                  const void *d_workspace, size_t workspace_bytes,
                                                  void *stream);
 
+/*
+ * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
+ * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
+ * is copied from host memory to GPU memory and decompressed there; Section 6 notes
+ * that the smaller transfers make overlap with other GPU work worthwhile).
+ *
+ * One blob = one compressed matrix (or a block of whole rows of one, see below) in
+ * HOST memory, preferably pinned (hipHostMalloc / torch pin_memory), and the device
+ * address its dense form goes to.
+ */
+typedef struct endor_host_blob {
+    int64_t rows;
+    int64_t cols;
+    const uint8_t *h_bitmap;  /* host: endor_bitmap_bytes(rows, cols) bytes readable */
+    const uint16_t *h_values; /* host: nnz elements */
+    int64_t nnz;
+    uint16_t *d_dense;        /* device out: rows*cols elements */
+} endor_host_blob;
+
+/* Bytes of ONE device staging buffer able to hold this blob's bitmap and values
+ * (each rounded up to 256 bytes).  0 on bad arguments. */
+size_t endor_stage_bytes(int64_t rows, int64_t cols, int64_t nnz);
+
+/*
+ * Double-buffered pipeline over `count` blobs: on `copy_stream` blob k is copied into
+ * staging buffer k%2 (hipMemcpyAsync) while `compute_stream` decompresses blob k-1 out
+ * of the other buffer; events order copy -> decompress of the same blob and
+ * decompress of blob k -> copy of blob k+2 into the buffer it frees.  Both streams must
+ * be non-NULL, distinct and of default priority.  d_stage[b] must hold the largest
+ * endor_stage_bytes of the blobs, d_workspace[b] the largest endor_workspace_bytes
+ * (both 256-byte aligned, not in use by earlier unfinished work).  Returns after
+ * enqueueing; the dense outputs are complete when compute_stream has drained.
+ *
+ * A matrix may be fed as several blobs of whole rows [r0, r1) for finer overlap:
+ * rows = r1-r0, h_bitmap = bitmap + r0*cols/8 (needs r0*cols % 64 == 0),
+ * h_values = values + row_offsets[r0], nnz = row_offsets[r1] - row_offsets[r0],
+ * d_dense = dense + r0*cols.  The bits after the block's last row in its final bitmap
+ * word belong to the next rows and are ignored, as pad bits are.
+ */
+endor_status endor_h2d_decompress_pipeline(const endor_host_blob *blobs, int count,
+                                           void *const d_stage[2], size_t stage_bytes,
+                                           void *const d_workspace[2], size_t workspace_bytes,
+                                           void *copy_stream, void *compute_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,6 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
+    "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
+        L.endor_stage_bytes.restype = _sz
+        L.endor_stage_bytes.argtypes = [_i64, _i64, _i64]
+        L.endor_h2d_decompress_pipeline.restype = ctypes.c_int
+        L.endor_h2d_decompress_pipeline.argtypes = [_p, ctypes.c_int, _p, _sz, _p, _sz, _p, _p]
         _lib = L
     return _lib
 
@@ -257,3 +262,72 @@ def decompress_batch_with_offsets(mats, workspace, outs=None, stream=None):
         outs = [_new_dense(m.rows, m.cols, mats[0].bitmap.device) for m in mats]
     _batch("endor_decompress_batch_with_offsets", mats, outs, workspace, stream)
     return outs
+
+
+# ------------------------------------------------------------------ host -> device pipeline
+
+class _HostBlob(ctypes.Structure):
+    _fields_ = [("rows", _i64), ("cols", _i64), ("h_bitmap", _p), ("h_values", _p),
+                ("nnz", _i64), ("d_dense", _p)]
+
+
+@dataclass
+class HostBlob:
+    """A compressed matrix, or a block of whole rows of one, in (pinned) host tensors."""
+    rows: int
+    cols: int
+    bitmap: object      # torch.uint8, host
+    values: object      # torch.int16, host
+    nnz: int
+    row_begin: int = 0  # first row of the block inside its matrix
+
+
+def stage_bytes(rows: int, cols: int, nnz: int) -> int:
+    return int(lib().endor_stage_bytes(rows, cols, nnz))
+
+
+def pin(c: Compressed):
+    """Copy a Compressed into pinned host tensors (allocated pinned, not registered)."""
+    torch = _torch()
+    bm = torch.empty(c.bitmap.size, dtype=torch.uint8, pin_memory=True)
+    bm.numpy()[:] = c.bitmap
+    vals = torch.empty(c.values.size, dtype=torch.int16, pin_memory=True)
+    vals.numpy()[:] = c.values.view(np.int16)
+    return bm, vals
+
+
+def row_blocks(c: Compressed, pinned, nblocks: int):
+    """Split one matrix into up to `nblocks` HostBlobs of whole rows.  Block starts are
+    rounded so that r0*cols is a multiple of 64 (a bitmap word boundary); the block's
+    values start at row_offsets[r0]."""
+    bm, vals = pinned
+    if c.row_offsets is None:
+        raise ValueError("row_blocks needs the compressor's row offsets")
+    rows, cols = c.rows, c.cols
+    step = 64 // int(np.gcd(cols, 64)) if cols else 1   # smallest r with r*cols % 64 == 0
+    cuts = sorted({min(rows, (rows * i // nblocks) // step * step) for i in range(nblocks)} | {rows})
+    if cuts[0] != 0:
+        cuts.insert(0, 0)
+    out = []
+    for r0, r1 in zip(cuts[:-1], cuts[1:]):
+        if r1 <= r0:
+            continue
+        k0, k1 = int(c.row_offsets[r0]), int(c.row_offsets[r1])
+        out.append(HostBlob(r1 - r0, cols, bm[r0 * cols // 8:], vals[k0:k1], k1 - k0, r0))
+    return out
+
+
+def h2d_decompress_pipeline(blobs, outs, stages, workspaces, copy_stream, compute_stream):
+    """endor_h2d_decompress_pipeline.  `outs[k]`: device tensor (or view) that receives blob k."""
+    arr = (_HostBlob * len(blobs))()
+    for i, b in enumerate(blobs):
+        arr[i].rows, arr[i].cols, arr[i].nnz = b.rows, b.cols, b.nnz
+        arr[i].h_bitmap = _dptr(b.bitmap)
+        arr[i].h_values = _dptr(b.values)
+        arr[i].d_dense = _dptr(outs[i])
+    st = (_p * 2)(_dptr(stages[0]), _dptr(stages[1]))
+    ws = (_p * 2)(_dptr(workspaces[0]), _dptr(workspaces[1]))
+    _check(lib().endor_h2d_decompress_pipeline(
+        ctypes.addressof(arr), len(blobs), ctypes.addressof(st), min(s.numel() for s in stages),
+        ctypes.addressof(ws), min(w.numel() for w in workspaces),
+        int(copy_stream.cuda_stream), int(compute_stream.cuda_stream)), "endor_h2d_decompress_pipeline")

@@ -12,6 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libendor.so")
 SOURCES = [os.path.join(HERE, "csrc", "endor_kernels.hip"),
+           os.path.join(HERE, "csrc", "endor_pipeline.hip"),
            os.path.join(HERE, "csrc", "endor_host.cpp")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -35,8 +35,15 @@ constexpr int kTileElems = ENDOR_TILE_ELEMS;  // flat positions per tile
 constexpr int kTileWords = kTileElems / 64;   // 64-bit bitmap words per tile (= lanes per wave)
 constexpr int kTilesPerChunk = 256;           // tiles one count workgroup covers
 constexpr int kChunkStride = kTilesPerChunk + 1;
-constexpr int kBlock = 256;                   // threads per workgroup of the offset kernels
+constexpr int kBlock = 256;                   // threads per workgroup of the row-offset kernel
 constexpr int kWaves = kBlock / 64;
+#ifndef ENDOR_COUNT_WAVES
+#define ENDOR_COUNT_WAVES 16
+#endif
+constexpr int kCountWaves = ENDOR_COUNT_WAVES;  // waves per workgroup of the tile-offset kernel
+constexpr int kCountBlock = 64 * kCountWaves;
+constexpr int kCountTilesPerWave = kTilesPerChunk / kCountWaves;
+constexpr int kCountSteps = kCountTilesPerWave / 2;  // two tiles per step
 // expand kernel launch shape (tunable at build time)
 #ifndef ENDOR_EXPAND_WAVES
 #define ENDOR_EXPAND_WAVES 1
@@ -69,7 +76,8 @@ constexpr int kStageRounds = (kStageChunks + 63) / 64;
 constexpr int64_t kMaxElems = int64_t(1) << 34;
 
 static_assert(kTileWords == 64, "one bitmap word per lane");
-static_assert(kTilesPerChunk == kBlock, "one tile count per thread in the chunk scan");
+static_assert(kCountBlock >= kTilesPerChunk && kCountTilesPerWave % 2 == 0 && kCountSteps >= 1,
+              "the tile-offset workgroup scans one tile count per thread");
 static_assert(kTilesPerChunk % kTilesPerBlock == 0, "expand workgroups do not straddle chunks");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -155,9 +163,13 @@ struct alignas(16) WordPair {
     uint64_t a, b;
 };
 
-__global__ __launch_bounds__(kBlock) void endor_tile_offsets_kernel(BatchParams P) {
+// Workgroup of kCountWaves waves per chunk; wave w popcounts tiles
+// [w*kCountTilesPerWave, (w+1)*kCountTilesPerWave) of the chunk in steps of two tiles
+// (128 words: lanes 0..31 hold tile 2i, lanes 32..63 tile 2i+1, two words per lane),
+// with all of its loads issued before the first popcount.
+__global__ __launch_bounds__(kCountBlock) void endor_tile_offsets_kernel(BatchParams P) {
     __shared__ uint32_t s_cnt[kTilesPerChunk];
-    __shared__ uint32_t s_wave[kWaves];
+    __shared__ uint32_t s_wave[kTilesPerChunk / 64];
 
     const uint32_t gc = blockIdx.x;
     const MatParams &M = P.m[find_matrix(P, gc)];
@@ -168,53 +180,53 @@ __global__ __launch_bounds__(kBlock) void endor_tile_offsets_kernel(BatchParams 
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
 
-    // this wave's 64 tiles = 4096 words; one step reads 128 words (two tiles):
-    // lanes 0..31 hold tile 2i, lanes 32..63 tile 2i+1, two words per lane
-    const int64_t wbase = (int64_t(c) * kTilesPerChunk + wave * 64) * kTileWords;
-    int64_t fast = (full_words - wbase) / 128;  // steps with all 128 words complete
-    fast = fast < 0 ? 0 : (fast > 32 ? 32 : fast);
-    const bool bitmap16 = (reinterpret_cast<uintptr_t>(bitmap) & 15) == 0;
+    const uint32_t t0 = wave * kCountTilesPerWave;  // first tile of this wave inside the chunk
+    const int64_t wbase = (int64_t(c) * kTilesPerChunk + t0) * kTileWords;
+    const bool all_fast = (reinterpret_cast<uintptr_t>(bitmap) & 15) == 0 &&
+                          wbase + kCountSteps * 128 <= full_words;  // wave-uniform
 
-    int i = 0;
-    if (bitmap16) {
-#pragma unroll 8
-        for (; i < static_cast<int>(fast); ++i) {
-#if ENDOR_NT_LOAD >= 3
-            const u32x4 wq = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(bitmap + wbase + i * 128 + lane * 2));
-            uint32_t p = __popc(wq.x) + __popc(wq.y) + __popc(wq.z) + __popc(wq.w);
-#else
-            const WordPair wp = *reinterpret_cast<const WordPair *>(bitmap + wbase + i * 128 + lane * 2);
-            uint32_t p = __popcll(wp.a) + __popcll(wp.b);
-#endif
-            p = row_inclusive_scan(p);
-            p += dpp_or_zero<0x142, 0xa>(p);
-            if ((lane & 31) == 31) s_cnt[wave * 64 + 2 * i + (lane >> 5)] = p;
+    uint32_t p[kCountSteps];
+    if (all_fast) {
+        WordPair wp[kCountSteps];
+#pragma unroll
+        for (int i = 0; i < kCountSteps; ++i)
+            wp[i] = *reinterpret_cast<const WordPair *>(bitmap + wbase + i * 128 + lane * 2);
+#pragma unroll
+        for (int i = 0; i < kCountSteps; ++i) p[i] = __popcll(wp[i].a) + __popcll(wp[i].b);
+    } else {
+#pragma unroll
+        for (int i = 0; i < kCountSteps; ++i) {
+            const int64_t w = wbase + i * 128 + lane * 2;
+            p[i] = __popcll(load_word_guarded(bitmap, w, full_words, tail_bits)) +
+                   __popcll(load_word_guarded(bitmap, w + 1, full_words, tail_bits));
         }
     }
-    for (; i < 32; ++i) {
-        const int64_t w = wbase + i * 128 + lane * 2;
-        uint32_t p = __popcll(load_word_guarded(bitmap, w, full_words, tail_bits)) +
-                     __popcll(load_word_guarded(bitmap, w + 1, full_words, tail_bits));
-        p = row_inclusive_scan(p);
-        p += dpp_or_zero<0x142, 0xa>(p);
-        if ((lane & 31) == 31) s_cnt[wave * 64 + 2 * i + (lane >> 5)] = p;
+#pragma unroll
+    for (int i = 0; i < kCountSteps; ++i) {
+        uint32_t q = row_inclusive_scan(p[i]);
+        q += dpp_or_zero<0x142, 0xa>(q);  // lanes 31 and 63 now hold the two tile counts
+        if ((lane & 31) == 31) s_cnt[t0 + 2 * i + (lane >> 5)] = q;
     }
     __syncthreads();
 
-    const uint32_t cnt = s_cnt[threadIdx.x];
-    const uint32_t incl = wave_inclusive_scan(cnt);
-    if (lane == 63) s_wave[wave] = incl;
+    if (threadIdx.x < kTilesPerChunk) {  // the first four waves scan the 256 tile counts
+        const uint32_t cnt = s_cnt[threadIdx.x];
+        const uint32_t incl = wave_inclusive_scan(cnt);
+        if (lane == 63) s_wave[wave] = incl;
+        s_cnt[threadIdx.x] = incl - cnt;
+    }
     __syncthreads();
-    uint32_t before = 0;
-    for (uint32_t v = 0; v < wave; ++v) before += s_wave[v];
-    const uint32_t excl = before + incl - cnt;
-
-    uint32_t *to = M.tile_off + size_t(c) * kChunkStride;
-    to[threadIdx.x] = excl;
-    if (threadIdx.x == kBlock - 1) {
-        to[kTilesPerChunk] = excl + cnt;
-        M.chunk_total[c] = excl + cnt;
+    if (threadIdx.x < kTilesPerChunk) {
+        uint32_t before = 0;
+        for (uint32_t v = 0; v < wave; ++v) before += s_wave[v];
+        const uint32_t excl = before + s_cnt[threadIdx.x];
+        uint32_t *to = M.tile_off + size_t(c) * kChunkStride;
+        to[threadIdx.x] = excl;
+        if (threadIdx.x == kTilesPerChunk - 1) {
+            const uint32_t total = before + s_wave[wave];
+            to[kTilesPerChunk] = total;
+            M.chunk_total[c] = total;
+        }
     }
 }
 
@@ -503,7 +515,7 @@ endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, s
         fill_group(mats + b, nb, need, ws, workspace_bytes, &off, &g);
         if (g.chunks == 0) continue;
         if (build) {
-            hipLaunchKernelGGL(endor_tile_offsets_kernel, dim3(g.chunks), dim3(kBlock), 0, s, g.P);
+            hipLaunchKernelGGL(endor_tile_offsets_kernel, dim3(g.chunks), dim3(kCountBlock), 0, s, g.P);
             if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
         }
         if (expand) {
