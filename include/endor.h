@@ -164,6 +164,38 @@ endor_status endor_decompress_batch_with_offsets(const endor_matrix *mats, int c
                                                  void *stream);
 
 /*
+ * 8-BIT ELEMENTS (Section 4.2, joint application with quantization): the same bitmap,
+ * one byte per value; the compressed size becomes rows*cols/8 + nnz bytes.  The offset
+ * table depends on the bitmap only, so endor_build_offsets, endor_workspace_bytes and
+ * endor_batch_workspace_bytes (which read rows and cols only) serve both widths.
+ * Arguments, alignment (1 byte for values and dense; 16 for the fast store path) and
+ * errors are as for the 16-bit entry points of the same name.
+ */
+typedef struct endor_matrix_u8 {
+    int64_t rows;
+    int64_t cols;
+    const uint8_t *d_bitmap;
+    const uint8_t *d_values; /* nnz bytes */
+    int64_t nnz;
+    uint8_t *d_dense;        /* out: rows*cols bytes */
+} endor_matrix_u8;
+
+endor_status endor_compress_u8(const uint8_t *dense, int64_t rows, int64_t cols,
+                               uint8_t *bitmap, uint8_t *values, int64_t values_capacity,
+                               int64_t *row_offsets, int64_t *nnz_out);
+endor_status endor_decompress_u8(int64_t rows, int64_t cols,
+                                 const uint8_t *d_bitmap, const uint8_t *d_values, int64_t nnz,
+                                 void *d_workspace, size_t workspace_bytes,
+                                 uint8_t *d_dense, void *stream);
+endor_status endor_decompress_u8_with_offsets(int64_t rows, int64_t cols,
+                                              const uint8_t *d_bitmap, const uint8_t *d_values,
+                                              int64_t nnz,
+                                              const void *d_workspace, size_t workspace_bytes,
+                                              uint8_t *d_dense, void *stream);
+endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, int count,
+                                       void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
  * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
  * is copied from host memory to GPU memory and decompressed there; Section 6 notes

@@ -65,16 +65,19 @@ def lib() -> ctypes.CDLL:
         L.endor_workspace_bytes.argtypes = [_i64, _i64]
         L.endor_batch_workspace_bytes.restype = _sz
         L.endor_batch_workspace_bytes.argtypes = [_p, ctypes.c_int]
-        L.endor_compress.restype = ctypes.c_int
-        L.endor_compress.argtypes = [_p, _i64, _i64, _p, _p, _i64, _p, _p]
+        for name in ("endor_compress", "endor_compress_u8"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [_p, _i64, _i64, _p, _p, _i64, _p, _p]
         L.endor_build_offsets.restype = ctypes.c_int
         L.endor_build_offsets.argtypes = [_i64, _i64, _p, _p, _sz, _p, _p]
-        L.endor_decompress.restype = ctypes.c_int
-        L.endor_decompress.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
-        L.endor_decompress_with_offsets.restype = ctypes.c_int
-        L.endor_decompress_with_offsets.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
+        for name in ("endor_decompress", "endor_decompress_with_offsets",
+                     "endor_decompress_u8", "endor_decompress_u8_with_offsets"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
         for name in ("endor_decompress_batch", "endor_build_offsets_batch",
-                     "endor_decompress_batch_with_offsets"):
+                     "endor_decompress_batch_with_offsets", "endor_decompress_batch_u8"):
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
@@ -107,7 +110,7 @@ class Compressed:
     rows: int
     cols: int
     bitmap: np.ndarray       # uint8[bitmap_bytes(rows, cols)]
-    values: np.ndarray       # uint16[nnz]
+    values: np.ndarray       # uint16[nnz], or uint8[nnz] for the 8-bit variant
     row_offsets: np.ndarray  # int64[rows + 1]
 
     @property
@@ -116,22 +119,25 @@ class Compressed:
 
 
 def compress(dense: np.ndarray, want_row_offsets: bool = True) -> Compressed:
-    """endor_compress on a 2-d array of 16-bit elements (float16 / int16 / uint16)."""
-    if dense.ndim != 2 or dense.dtype.itemsize != 2:
-        raise ValueError("dense must be a 2-d array of 16-bit elements")
-    W = np.ascontiguousarray(dense).view(np.uint16)
+    """endor_compress / endor_compress_u8 on a 2-d array of 16-bit (float16 / int16 /
+    uint16) or 8-bit (int8 / uint8) elements."""
+    if dense.ndim != 2 or dense.dtype.itemsize not in (1, 2):
+        raise ValueError("dense must be a 2-d array of 8- or 16-bit elements")
+    wide = dense.dtype.itemsize == 2
+    W = np.ascontiguousarray(dense).view(np.uint16 if wide else np.uint8)
     rows, cols = W.shape
     L = lib()
+    fn = L.endor_compress if wide else L.endor_compress_u8
     bitmap = np.empty(bitmap_bytes(rows, cols), dtype=np.uint8)
     row_offsets = np.empty(rows + 1, dtype=np.int64) if want_row_offsets else None
     nnz = _i64(0)
     ro = row_offsets.ctypes.data if want_row_offsets else None
     # counting pass, then the packing pass into an exactly sized buffer
-    _check(L.endor_compress(W.ctypes.data, rows, cols, bitmap.ctypes.data, None, 0, ro,
-                            ctypes.byref(nnz)), "endor_compress(count)")
-    values = np.empty(nnz.value, dtype=np.uint16)
-    _check(L.endor_compress(W.ctypes.data, rows, cols, bitmap.ctypes.data, values.ctypes.data,
-                            values.size, ro, ctypes.byref(nnz)), "endor_compress")
+    _check(fn(W.ctypes.data, rows, cols, bitmap.ctypes.data, None, 0, ro, ctypes.byref(nnz)),
+           "endor_compress(count)")
+    values = np.empty(nnz.value, dtype=W.dtype)
+    _check(fn(W.ctypes.data, rows, cols, bitmap.ctypes.data, values.ctypes.data, values.size, ro,
+              ctypes.byref(nnz)), "endor_compress")
     return Compressed(rows, cols, bitmap, values, row_offsets)
 
 
@@ -159,14 +165,18 @@ class DeviceMatrix:
     rows: int
     cols: int
     bitmap: object   # torch.uint8[bitmap_bytes]
-    values: object   # torch.int16[nnz]
+    values: object   # torch.int16[nnz] (16-bit elements) or torch.uint8[nnz] (8-bit)
     nnz: int
+
+    @property
+    def elem_bytes(self) -> int:
+        return int(self.values.element_size())
 
 
 def to_device(c: Compressed, device="cuda") -> DeviceMatrix:
     torch = _torch()
     bm = torch.from_numpy(c.bitmap).to(device)
-    vals = torch.from_numpy(c.values.view(np.int16)).to(device)
+    vals = torch.from_numpy(c.values.view(np.int16 if c.values.dtype.itemsize == 2 else np.uint8)).to(device)
     return DeviceMatrix(c.rows, c.cols, bm, vals, c.nnz)
 
 
@@ -175,9 +185,9 @@ def _new_workspace(nbytes: int, device):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
-def _new_dense(rows, cols, device):
+def _new_dense(rows, cols, device, elem_bytes=2):
     torch = _torch()
-    return torch.empty((rows, cols), dtype=torch.int16, device=device)
+    return torch.empty((rows, cols), dtype=torch.int16 if elem_bytes == 2 else torch.uint8, device=device)
 
 
 def build_offsets(m: DeviceMatrix, workspace=None, row_offsets: bool = False, stream=None):
@@ -195,22 +205,25 @@ def build_offsets(m: DeviceMatrix, workspace=None, row_offsets: bool = False, st
 def decompress(m: DeviceMatrix, out=None, workspace=None, stream=None):
     """endor_decompress.  `out`: any 2-byte-element tensor of rows*cols elements."""
     if out is None:
-        out = _new_dense(m.rows, m.cols, m.bitmap.device)
+        out = _new_dense(m.rows, m.cols, m.bitmap.device, m.elem_bytes)
     if workspace is None:
         workspace = _new_workspace(workspace_bytes(m.rows, m.cols), m.bitmap.device)
-    _check(lib().endor_decompress(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz,
-                                  _dptr(workspace), workspace.numel(), _dptr(out),
-                                  _stream_handle(stream)), "endor_decompress")
+    if out.element_size() != m.elem_bytes:
+        raise ValueError("output element width differs from the values'")
+    fn = lib().endor_decompress if m.elem_bytes == 2 else lib().endor_decompress_u8
+    _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(workspace),
+              workspace.numel(), _dptr(out), _stream_handle(stream)), "endor_decompress")
     return out
 
 
 def decompress_with_offsets(m: DeviceMatrix, workspace, out=None, stream=None):
     if out is None:
-        out = _new_dense(m.rows, m.cols, m.bitmap.device)
-    _check(lib().endor_decompress_with_offsets(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values),
-                                               m.nnz, _dptr(workspace), workspace.numel(),
-                                               _dptr(out), _stream_handle(stream)),
-           "endor_decompress_with_offsets")
+        out = _new_dense(m.rows, m.cols, m.bitmap.device, m.elem_bytes)
+    if out.element_size() != m.elem_bytes:
+        raise ValueError("output element width differs from the values'")
+    fn = lib().endor_decompress_with_offsets if m.elem_bytes == 2 else lib().endor_decompress_u8_with_offsets
+    _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(workspace),
+              workspace.numel(), _dptr(out), _stream_handle(stream)), "endor_decompress_with_offsets")
     return out
 
 
@@ -242,11 +255,14 @@ def decompress_batch(mats, outs=None, workspace=None, stream=None):
     if not mats:
         return [], workspace
     dev = mats[0].bitmap.device
+    eb = mats[0].elem_bytes
+    if any(m.elem_bytes != eb for m in mats):
+        raise ValueError("one batch holds one element width")
     if outs is None:
-        outs = [_new_dense(m.rows, m.cols, dev) for m in mats]
+        outs = [_new_dense(m.rows, m.cols, dev, eb) for m in mats]
     if workspace is None:
         workspace = _new_workspace(batch_workspace_bytes(mats), dev)
-    _batch("endor_decompress_batch", mats, outs, workspace, stream)
+    _batch("endor_decompress_batch" if eb == 2 else "endor_decompress_batch_u8", mats, outs, workspace, stream)
     return outs, workspace
 
 

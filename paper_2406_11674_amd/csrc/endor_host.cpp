@@ -50,7 +50,26 @@ inline uint64_t nonzero_mask64(const uint16_t *d) {
 #endif
 }
 
-inline uint64_t nonzero_mask_tail(const uint16_t *d, int count) {
+// the same for 64 consecutive one-byte elements
+inline uint64_t nonzero_mask64(const uint8_t *d) {
+#if defined(__SSE2__)
+    const __m128i zero = _mm_setzero_si128();
+    uint64_t m = 0;
+    for (int g = 0; g < 4; ++g) {
+        __m128i a = _mm_loadu_si128(reinterpret_cast<const __m128i *>(d + 16 * g));
+        uint64_t zeros = static_cast<uint32_t>(_mm_movemask_epi8(_mm_cmpeq_epi8(a, zero)));
+        m |= ((~zeros) & 0xFFFFull) << (16 * g);
+    }
+    return m;
+#else
+    uint64_t m = 0;
+    for (int i = 0; i < 64; ++i) m |= uint64_t(d[i] != 0) << i;
+    return m;
+#endif
+}
+
+template <class T>
+inline uint64_t nonzero_mask_tail(const T *d, int count) {
     uint64_t m = 0;
     for (int i = 0; i < count; ++i) m |= uint64_t(d[i] != 0) << i;
     return m;
@@ -94,9 +113,11 @@ extern "C" size_t endor_bitmap_bytes(int64_t rows, int64_t cols) {
     return static_cast<size_t>((n + 63) / 64) * 8;
 }
 
-extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int64_t cols,
-                                       uint8_t *bitmap, uint16_t *values, int64_t values_capacity,
-                                       int64_t *row_offsets, int64_t *nnz_out) {
+namespace {
+
+template <class T>
+endor_status compress_impl(const T *dense, int64_t rows, int64_t cols, uint8_t *bitmap, T *values,
+                           int64_t values_capacity, int64_t *row_offsets, int64_t *nnz_out) {
     if (rows < 0 || cols < 0 || values_capacity < 0) return ENDOR_ERR_INVALID_ARG;
     if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
     const int64_t n = rows * cols;
@@ -161,9 +182,9 @@ extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int6
                 ++next_row;
             }
             if (pack) {
-                const uint16_t *d = dense + e0;
+                const T *d = dense + e0;
                 if (m == ~uint64_t(0)) {
-                    std::memcpy(values + k, d, 128);
+                    std::memcpy(values + k, d, 64 * sizeof(T));
                     k += 64;
                 } else {
                     uint64_t mm = m;
@@ -180,4 +201,18 @@ extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int6
     if (row_offsets) row_offsets[rows] = nnz;
     if (values != nullptr && nnz > values_capacity) return ENDOR_ERR_BUFFER_TOO_SMALL;
     return ENDOR_OK;
+}
+
+}  // namespace
+
+extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int64_t cols,
+                                       uint8_t *bitmap, uint16_t *values, int64_t values_capacity,
+                                       int64_t *row_offsets, int64_t *nnz_out) {
+    return compress_impl<uint16_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+}
+
+extern "C" endor_status endor_compress_u8(const uint8_t *dense, int64_t rows, int64_t cols,
+                                          uint8_t *bitmap, uint8_t *values, int64_t values_capacity,
+                                          int64_t *row_offsets, int64_t *nnz_out) {
+    return compress_impl<uint8_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
 }

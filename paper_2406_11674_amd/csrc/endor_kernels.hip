@@ -11,8 +11,9 @@
 //      words).  One workgroup covers a chunk of 256 tiles: it popcounts the chunk's
 //      128 KiB of bitmap, scans the 256 tile counts and stores the tile offsets
 //      relative to the chunk start plus the chunk's total.
-//   2. endor_expand_kernel: one wave per tile, waves fully independent (no
-//      workgroup barrier).  The wave adds up the totals of the chunks before its
+//   2. endor_expand_kernel: one single-wave workgroup per tile, waves fully
+//      independent (no workgroup barrier; measured faster on MI355X than wider
+//      workgroups or several tiles per wave).  The wave adds up the totals of the chunks before its
 //      own (a few loads per lane) to get the chunk's absolute start, stages the
 //      tile's contiguous slice of `values` into LDS with 16-byte loads, scans the
 //      64 word popcounts across lanes (DPP), and then, in 8 steps of 512 elements,
@@ -54,25 +55,14 @@ constexpr int kCountSteps = kCountTilesPerWave / 2;  // two tiles per step
 #ifndef ENDOR_NT_LOAD
 #define ENDOR_NT_LOAD 1  // 1: values are read once, stream them; the bitmap is read twice and stays cacheable
 #endif
-#ifndef ENDOR_INTERLEAVE
-#define ENDOR_INTERLEAVE 0
-#endif
 #ifndef ENDOR_NT_STORE
 #define ENDOR_NT_STORE 1
-#endif
-#ifndef ENDOR_XCD_REMAP
-#define ENDOR_XCD_REMAP 0
-#endif
-#ifndef ENDOR_LDS_PAD
-#define ENDOR_LDS_PAD 0
 #endif
 constexpr int kExpandWaves = ENDOR_EXPAND_WAVES;   // waves per expand workgroup
 constexpr int kExpandBlock = 64 * kExpandWaves;
 constexpr int kTilesPerWave = ENDOR_TILES_PER_WAVE;  // tiles one expand wave walks
 constexpr int kTilesPerBlock = kExpandWaves * kTilesPerWave;
 constexpr int kBlocksPerChunk = kTilesPerChunk / kTilesPerBlock;
-constexpr int kStageChunks = (2 * (7 + kTileElems + 7) + 15) / 16;  // 16-byte units of LDS value staging
-constexpr int kStageRounds = (kStageChunks + 63) / 64;
 constexpr int64_t kMaxElems = int64_t(1) << 34;
 
 static_assert(kTileWords == 64, "one bitmap word per lane");
@@ -84,8 +74,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct MatParams {
     const uint64_t *bitmap;
-    const uint16_t *values;
-    uint16_t *dense;
+    const void *values;     // nnz elements of 1 or 2 bytes
+    void *dense;            // rows*cols elements of the same width
     uint32_t *chunk_total;  // [nchunks] 1 bits per chunk
     uint32_t *tile_off;     // [nchunks][257] 1 bits before each tile, relative to the chunk start
     int64_t n;              // rows*cols
@@ -97,7 +87,6 @@ struct MatParams {
 struct BatchParams {
     MatParams m[ENDOR_MAX_BATCH];
     int count;
-    uint32_t total_blocks;  // expand workgroups that have work
 };
 
 // ---------------------------------------------------------------- wave primitives
@@ -131,10 +120,9 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
 
 // Bitmap word `w` of a matrix with `full_words` complete words and `tail_bits`
 // valid bits in the word after them; pad bits and words past the end read as 0.
-template <bool kStream = false>
 __device__ __forceinline__ uint64_t load_word_guarded(const uint64_t *bitmap, int64_t w,
                                                       int64_t full_words, uint32_t tail_bits) {
-    if (w < full_words) return kStream ? __builtin_nontemporal_load(bitmap + w) : bitmap[w];
+    if (w < full_words) return bitmap[w];
     if (w == full_words && tail_bits != 0) return bitmap[w] & ((uint64_t(1) << tail_bits) - 1);
     return 0;
 }
@@ -232,50 +220,163 @@ __global__ __launch_bounds__(kCountBlock) void endor_tile_offsets_kernel(BatchPa
 
 // ---------------------------------------------------------------- kernel 2: expand
 
+// Element width E in bytes: 2 (fp16, the paper's main case) or 1 (the 8-bit variant of
+// Section 4.2).  A lane produces 16 bytes of output per step, i.e. kLaneElems elements
+// covering kLaneElems bitmap bits; a tile of 4096 elements takes kSteps steps.
+template <int E>
+struct Shape {
+    static constexpr int kLaneElems = 16 / E;                  // 8 or 16
+    static constexpr int kSteps = kTileElems / (64 * kLaneElems);  // 8 or 4
+    static constexpr int kLanesPerWord = 64 / kLaneElems;      // 8 or 4
+    // LDS staging of the tile's value slice in 16-byte units: up to kLaneElems-1 elements
+    // of alignment slack in front, 4096 values, and kLaneElems-1 elements a lane may
+    // read past its last value (those reads are masked off by the bits)
+    static constexpr int kStageChunks = (E * (2 * (kLaneElems - 1) + kTileElems) + 15) / 16;
+    static constexpr int kStageRounds = (kStageChunks + 63) / 64;
+};
+
+template <int E>
 struct alignas(16) WaveScratch {
-    u32x4 stage[kStageChunks];   // the tile's slice of `values`, from the 16-byte boundary below it
-    uint64_t words[kTileWords];  // the tile's bitmap words
-    uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
+    u32x4 stage[Shape<E>::kStageChunks];  // the tile's slice of `values`, from the 16-byte boundary below it
+    uint64_t words[kTileWords];           // the tile's bitmap words
+    uint32_t start[kTileWords];           // per word: index into `stage` (in elements) of its first value
 };
 
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
+template <int E>
 __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
 #if ENDOR_NT_LOAD
     if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 #else
     if (p >= vbeg && p + 16 <= vend) return *reinterpret_cast<const u32x4 *>(p);
 #endif
-    uint32_t h[8];
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uintptr_t q = p + 2 * j;
-        h[j] = (q >= vbeg && q + 2 <= vend) ? *reinterpret_cast<const uint16_t *>(q) : 0u;
+    for (int j = 0; j < 16 / E; ++j) {
+        const uintptr_t q = p + E * j;
+        uint32_t v = 0;
+        if (q >= vbeg && q + E <= vend)
+            v = (E == 2) ? uint32_t(*reinterpret_cast<const uint16_t *>(q)) : uint32_t(*reinterpret_cast<const uint8_t *>(q));
+        d[(E * j) >> 2] |= v << (8 * ((E * j) & 3));
     }
     u32x4 r;
-    r.x = h[0] | (h[1] << 16);
-    r.y = h[2] | (h[3] << 16);
-    r.z = h[4] | (h[5] << 16);
-    r.w = h[6] | (h[7] << 16);
+    r.x = d[0];
+    r.y = d[1];
+    r.z = d[2];
+    r.w = d[3];
     return r;
 }
 
-template <bool kAlignedOut>
-__global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams P) {
-    __shared__ WaveScratch s_scratch[kExpandWaves];
-#if ENDOR_LDS_PAD
-    __shared__ uint32_t s_pad[ENDOR_LDS_PAD / 4];
-    if (P.count < 0) s_pad[threadIdx.x] = 1;  // never true; keeps the padding allocated
-#endif
-#if ENDOR_XCD_REMAP
-    // workgroups are handed to the 8 XCDs round-robin; give each XCD one contiguous range
-    const uint32_t per_xcd = gridDim.x / 8;
-    const uint32_t bid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (bid >= P.total_blocks) return;
+// 0xffff in the halves whose bit is set: bits 0,1 of `b` -> low, high half
+__device__ __forceinline__ uint32_t half_mask(uint32_t b) {
+    return ((b & 1u) ? 0xffffu : 0u) | ((b & 2u) ? 0xffff0000u : 0u);
+}
+// 0xff in the bytes whose bit is set: bits 0..3 of `b`
+__device__ __forceinline__ uint32_t byte_mask(uint32_t b) {
+    return ((b & 1u) ? 0xffu : 0u) | ((b & 2u) ? 0xff00u : 0u) | ((b & 4u) ? 0xff0000u : 0u) |
+           ((b & 8u) ? 0xff000000u : 0u);
+}
+
+// Expand one tile with one wave.
+//   word     this lane's 64 bitmap bits of the tile (bits past the end already cleared)
+//   vaddr    byte address of the tile's first value; cnt = number of 1 bits in the tile
+//   [vbeg, vend)  the byte range of the whole `values` array (nothing outside is read)
+//   out      byte address of the tile's first output element; nvalid <= 4096 elements are written
+// The caller has not touched S since the wave's previous call returned.
+template <int E, bool kAlignedOut>
+__device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, uint64_t word, uintptr_t vaddr,
+                                            uint32_t cnt, uintptr_t vbeg, uintptr_t vend, uint8_t *out,
+                                            uint32_t nvalid) {
+    using Sh = Shape<E>;
+    // --- issue the loads of the tile's value slice (16-byte units from the 16-byte
+    //     boundary at or below its first value)
+    const uintptr_t a16 = vaddr & ~uintptr_t(15);
+    const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
+    cnt = cnt > kTileElems ? kTileElems : cnt;  // a stale or foreign table must not overrun the staging area
+    const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
+    u32x4 r[Sh::kStageRounds];
+#pragma unroll
+    for (int q = 0; q < Sh::kStageRounds; ++q) {
+        const uint32_t ch = q * 64 + lane;
+        if (ch < nch) r[q] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
+    }
+
+    // --- popcount of this lane's word, scan across the wave
+    const uint32_t pc = __popcll(word);
+    const uint32_t incl = wave_inclusive_scan(pc);
+    S.words[lane] = word;
+    S.start[lane] = incl - pc + shift;
+#pragma unroll
+    for (int q = 0; q < Sh::kStageRounds; ++q) {
+        const uint32_t ch = q * 64 + lane;
+        if (ch < nch) S.stage[ch] = r[q];
+    }
+    // LDS operations of one wave execute in issue order, so the reads below see the
+    // writes above; the fences only keep the compiler from moving them.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // --- expand: per step every lane turns kLaneElems bitmap bits into 16 bytes of output
+    const bool full_tile = nvalid == kTileElems;
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) {
+        const uint32_t wi = k * Sh::kLaneElems + lane / Sh::kLanesPerWord;
+        const uint64_t w = S.words[wi];
+        const uint32_t sh = (lane % Sh::kLanesPerWord) * Sh::kLaneElems;
+        const uint32_t bits = static_cast<uint32_t>(w >> sh) & ((1u << Sh::kLaneElems) - 1);
+        const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
+        u32x4 d;
+        if (E == 2) {
+            const uint16_t *sp = reinterpret_cast<const uint16_t *>(S.stage) + s;
+            uint32_t h[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
+            d.x = (h[0] | (h[1] << 16)) & half_mask(bits);
+            d.y = (h[2] | (h[3] << 16)) & half_mask(bits >> 2);
+            d.z = (h[4] | (h[5] << 16)) & half_mask(bits >> 4);
+            d.w = (h[6] | (h[7] << 16)) & half_mask(bits >> 6);
+        } else {
+            const uint8_t *sp = reinterpret_cast<const uint8_t *>(S.stage) + s;
+            uint32_t h[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
+            d.x = (h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24)) & byte_mask(bits);
+            d.y = (h[4] | (h[5] << 8) | (h[6] << 16) | (h[7] << 24)) & byte_mask(bits >> 4);
+            d.z = (h[8] | (h[9] << 8) | (h[10] << 16) | (h[11] << 24)) & byte_mask(bits >> 8);
+            d.w = (h[12] | (h[13] << 8) | (h[14] << 16) | (h[15] << 24)) & byte_mask(bits >> 12);
+        }
+        const uint32_t le = (k * 64 + lane) * Sh::kLaneElems;  // element index inside the tile
+        if (kAlignedOut && full_tile) {
+#if ENDOR_NT_STORE
+            __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + size_t(le) * E));
 #else
-    const uint32_t bid = blockIdx.x;
+            *reinterpret_cast<u32x4 *>(out + size_t(le) * E) = d;
 #endif
-    const uint32_t gc = bid / kBlocksPerChunk;
-    const uint32_t sub = bid % kBlocksPerChunk;
+        } else {
+            const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int j = 0; j < Sh::kLaneElems; ++j) {
+                if (le + j < nvalid) {
+                    const uint32_t v = dd[(E * j) >> 2] >> (8 * ((E * j) & 3));
+                    if (E == 2)
+                        reinterpret_cast<uint16_t *>(out)[le + j] = static_cast<uint16_t>(v);
+                    else
+                        out[le + j] = static_cast<uint8_t>(v);
+                }
+            }
+        }
+    }
+    // the next tile's LDS writes must stay behind this tile's LDS reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int E, bool kAlignedOut>
+__global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams P) {
+    __shared__ WaveScratch<E> s_scratch[kExpandWaves];
+    const uint32_t gc = blockIdx.x / kBlocksPerChunk;
+    const uint32_t sub = blockIdx.x % kBlocksPerChunk;
     const MatParams &M = P.m[find_matrix(P, gc)];
     const uint32_t c = gc - M.chunk_begin;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -283,103 +384,28 @@ __global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams 
 
     const int64_t n = M.n;
     const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
-    // first tile of this wave, relative to the chunk, and the step to its next one
-#if ENDOR_INTERLEAVE
-    const uint32_t tl0 = sub * kTilesPerBlock + wave;
-    constexpr int kTileStep = kExpandWaves;
-#else
-    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;
-    constexpr int kTileStep = 1;
-#endif
+    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;  // first tile, relative to the chunk
     const int64_t tile0 = int64_t(c) * kTilesPerChunk + tl0;
     if (tile0 >= ntiles) return;  // whole wave; the kernel has no workgroup barrier
 
-    const uint64_t *bitmap = M.bitmap;
     const int64_t full_words = n >> 6;
     const uint32_t tail_bits = static_cast<uint32_t>(n & 63);
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(M.values);
-    const uintptr_t vend = vbeg + 2 * static_cast<uintptr_t>(M.nnz);
+    const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(M.nnz);
     const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl0;
     const uint64_t base = chunk_base(M.chunk_total, c, lane);
-    WaveScratch &S = s_scratch[wave];
-    const uint16_t *stage16 = reinterpret_cast<const uint16_t *>(S.stage);
 
     for (int t = 0; t < kTilesPerWave; ++t) {
-        const int64_t tile = tile0 + t * kTileStep;
+        const int64_t tile = tile0 + t;
         if (tile >= ntiles) break;
-        const uint32_t o0 = tile_off[t * kTileStep];
-        uint32_t cnt = tile_off[t * kTileStep + 1] - o0;  // 1 bits in this tile
-        cnt = cnt > kTileElems ? kTileElems : cnt;  // a stale or foreign table must not overrun the staging area
-
-        // --- issue the loads of the tile's value slice (16-byte units from the
-        //     16-byte boundary at or below its first value)
-        const uintptr_t a = vbeg + 2 * (base + o0);
-        const uintptr_t a16 = a & ~uintptr_t(15);
-        const uint32_t shift = static_cast<uint32_t>(a - a16) >> 1;           // 0..7 elements
-        const uint32_t nch = cnt ? ((shift + cnt + 7) >> 3) : 0;              // <= kStageChunks - 1
-        u32x4 r[kStageRounds];
-#pragma unroll
-        for (int q = 0; q < kStageRounds; ++q) {
-            const uint32_t ch = q * 64 + lane;
-            if (ch < nch) r[q] = load_values16(a16 + 16 * uintptr_t(ch), vbeg, vend);
-        }
-
-        // --- bitmap word of this lane, popcount, scan across the wave
-        const uint64_t word =
-            load_word_guarded<(ENDOR_NT_LOAD >= 2)>(bitmap, tile * kTileWords + lane, full_words, tail_bits);
-        const uint32_t pc = __popcll(word);
-        const uint32_t incl = wave_inclusive_scan(pc);
-        S.words[lane] = word;
-        S.start[lane] = incl - pc + shift;
-
-#pragma unroll
-        for (int q = 0; q < kStageRounds; ++q) {
-            const uint32_t ch = q * 64 + lane;
-            if (ch < nch) S.stage[ch] = r[q];
-        }
-        // LDS operations of one wave execute in issue order, so the reads below see
-        // the writes above; the fence only keeps the compiler from moving them.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        // --- expand: 8 steps of 512 elements; lane handles bitmap byte k*64+lane
+        const uint32_t o0 = tile_off[t];
+        const uint32_t cnt = tile_off[t + 1] - o0;  // 1 bits in this tile
+        const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
         const int64_t e0 = tile * kTileElems;
-        const bool full_tile = e0 + kTileElems <= n;
-        uint16_t *out = M.dense + e0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const uint32_t wi = k * 8 + (lane >> 3);
-            const uint64_t w = S.words[wi];
-            const uint32_t sh = (lane & 7) * 8;
-            const uint32_t byte = static_cast<uint32_t>(w >> sh) & 0xffu;
-            const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
-            const uint16_t *sp = stage16 + s;
-            uint32_t h[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = sp[__popc(byte & ((1u << j) - 1))];
-            u32x4 d;
-            d.x = (h[0] | (h[1] << 16)) & (((byte & 1u) ? 0xffffu : 0u) | ((byte & 2u) ? 0xffff0000u : 0u));
-            d.y = (h[2] | (h[3] << 16)) & (((byte & 4u) ? 0xffffu : 0u) | ((byte & 8u) ? 0xffff0000u : 0u));
-            d.z = (h[4] | (h[5] << 16)) & (((byte & 16u) ? 0xffffu : 0u) | ((byte & 32u) ? 0xffff0000u : 0u));
-            d.w = (h[6] | (h[7] << 16)) & (((byte & 64u) ? 0xffffu : 0u) | ((byte & 128u) ? 0xffff0000u : 0u));
-            const uint32_t le = (k * 64 + lane) * 8;  // element index inside the tile
-            if (kAlignedOut && full_tile) {
-#if ENDOR_NT_STORE
-                __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + le));
-#else
-                *reinterpret_cast<u32x4 *>(out + le) = d;
-#endif
-            } else {
-                const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (e0 + le + j < n) out[le + j] = static_cast<uint16_t>(dd[j >> 1] >> (16 * (j & 1)));
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        const int64_t left = n - e0;
+        expand_tile<E, kAlignedOut>(s_scratch[wave], lane, word, vbeg + E * (base + o0), cnt, vbeg, vend,
+                                    reinterpret_cast<uint8_t *>(M.dense) + e0 * E,
+                                    left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems));
     }
 }
 
@@ -444,8 +470,9 @@ enum Need { kNeedBitmap = 1, kNeedValuesDense = 2 };
 
 // Validate `count` matrices starting at the workspace offset *ws_off and fill one
 // launch group.  Advances *ws_off past the slices it used.
-endor_status fill_group(const endor_matrix *mats, int count, int need, char *ws, size_t ws_bytes,
-                        size_t *ws_off, Group *g) {
+endor_status fill_group(const endor_matrix *mats, int count, int need, int elem_bytes, char *ws,
+                        size_t ws_bytes, size_t *ws_off, Group *g) {
+    const uintptr_t elem_mask = static_cast<uintptr_t>(elem_bytes - 1);
     g->P.count = 0;
     g->chunks = 0;
     g->aligned_out = true;
@@ -458,8 +485,8 @@ endor_status fill_group(const endor_matrix *mats, int count, int need, char *ws,
         if (!m.d_bitmap || (reinterpret_cast<uintptr_t>(m.d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
         if (need & kNeedValuesDense) {
             if (m.nnz < 0 || m.nnz > n) return ENDOR_ERR_INVALID_ARG;
-            if (!m.d_dense || (reinterpret_cast<uintptr_t>(m.d_dense) & 1)) return ENDOR_ERR_INVALID_ARG;
-            if (m.nnz > 0 && (!m.d_values || (reinterpret_cast<uintptr_t>(m.d_values) & 1)))
+            if (!m.d_dense || (reinterpret_cast<uintptr_t>(m.d_dense) & elem_mask)) return ENDOR_ERR_INVALID_ARG;
+            if (m.nnz > 0 && (!m.d_values || (reinterpret_cast<uintptr_t>(m.d_values) & elem_mask)))
                 return ENDOR_ERR_INVALID_ARG;
             if (reinterpret_cast<uintptr_t>(m.d_dense) & 15) g->aligned_out = false;
         }
@@ -482,8 +509,19 @@ endor_status fill_group(const endor_matrix *mats, int count, int need, char *ws,
     return ENDOR_OK;
 }
 
+template <int E>
+void launch_expand(const Group &g, hipStream_t s) {
+    const dim3 grid(g.chunks * kBlocksPerChunk);
+    if (g.aligned_out)
+        hipLaunchKernelGGL((endor_expand_kernel<E, true>), grid, dim3(kExpandBlock), 0, s, g.P);
+    else
+        hipLaunchKernelGGL((endor_expand_kernel<E, false>), grid, dim3(kExpandBlock), 0, s, g.P);
+}
+
+// The shared driver of every device entry point.  `mats` holds 16-bit typed pointers;
+// with elem_bytes == 1 they are really 8-bit (endor_matrix_u8 has the same layout).
 endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, size_t workspace_bytes,
-                       void *stream, bool build, bool expand) {
+                       void *stream, bool build, bool expand, int elem_bytes = 2) {
     if (count < 0 || (count > 0 && !mats)) return ENDOR_ERR_INVALID_ARG;
     if (count == 0) return ENDOR_OK;
     for (int i = 0; i < count; ++i) {
@@ -504,7 +542,7 @@ endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, s
         Group g;
         for (int b = 0; b < count; b += ENDOR_MAX_BATCH) {
             const int nb = count - b < ENDOR_MAX_BATCH ? count - b : ENDOR_MAX_BATCH;
-            endor_status st = fill_group(mats + b, nb, need, ws, workspace_bytes, &off, &g);
+            endor_status st = fill_group(mats + b, nb, need, elem_bytes, ws, workspace_bytes, &off, &g);
             if (st != ENDOR_OK) return st;
         }
     }
@@ -512,23 +550,17 @@ endor_status run_batch(const endor_matrix *mats, int count, void *d_workspace, s
     Group g;
     for (int b = 0; b < count; b += ENDOR_MAX_BATCH) {
         const int nb = count - b < ENDOR_MAX_BATCH ? count - b : ENDOR_MAX_BATCH;
-        fill_group(mats + b, nb, need, ws, workspace_bytes, &off, &g);
+        fill_group(mats + b, nb, need, elem_bytes, ws, workspace_bytes, &off, &g);
         if (g.chunks == 0) continue;
         if (build) {
             hipLaunchKernelGGL(endor_tile_offsets_kernel, dim3(g.chunks), dim3(kCountBlock), 0, s, g.P);
             if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
         }
         if (expand) {
-            g.P.total_blocks = g.chunks * kBlocksPerChunk;
-#if ENDOR_XCD_REMAP
-            const dim3 grid((g.P.total_blocks + 7) / 8 * 8);
-#else
-            const dim3 grid(g.P.total_blocks);
-#endif
-            if (g.aligned_out)
-                hipLaunchKernelGGL(endor_expand_kernel<true>, grid, dim3(kExpandBlock), 0, s, g.P);
+            if (elem_bytes == 2)
+                launch_expand<2>(g, s);
             else
-                hipLaunchKernelGGL(endor_expand_kernel<false>, grid, dim3(kExpandBlock), 0, s, g.P);
+                launch_expand<1>(g, s);
             if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
         }
     }
@@ -608,7 +640,7 @@ extern "C" endor_status endor_build_offsets(int64_t rows, int64_t cols, const ui
     if (n > 0) {
         size_t off = 0;
         Group g;
-        fill_group(&m, 1, kNeedBitmap, static_cast<char *>(d_workspace), workspace_bytes, &off, &g);
+        fill_group(&m, 1, kNeedBitmap, 2, static_cast<char *>(d_workspace), workspace_bytes, &off, &g);
         M = g.P.m[0];
     }
     // n == 0: nchunks == 0 and every position is >= ntiles, so all entries are 0
@@ -618,4 +650,31 @@ extern "C" endor_status endor_build_offsets(int64_t rows, int64_t cols, const ui
     hipLaunchKernelGGL(endor_row_offsets_kernel, dim3(blocks), dim3(kBlock), 0, s, M, rows, cols, d_row_offsets);
     if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
     return ENDOR_OK;
+}
+
+// ---------------------------------------------------------------- 8-bit elements (Section 4.2)
+
+static_assert(sizeof(endor_matrix_u8) == sizeof(endor_matrix), "same descriptor layout for both widths");
+
+extern "C" endor_status endor_decompress_u8(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                            const uint8_t *d_values, int64_t nnz, void *d_workspace,
+                                            size_t workspace_bytes, uint8_t *d_dense, void *stream) {
+    const endor_matrix m = one_matrix(rows, cols, d_bitmap, reinterpret_cast<const uint16_t *>(d_values), nnz,
+                                      reinterpret_cast<uint16_t *>(d_dense));
+    return run_batch(&m, 1, d_workspace, workspace_bytes, stream, true, true, 1);
+}
+
+extern "C" endor_status endor_decompress_u8_with_offsets(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                                         const uint8_t *d_values, int64_t nnz,
+                                                         const void *d_workspace, size_t workspace_bytes,
+                                                         uint8_t *d_dense, void *stream) {
+    const endor_matrix m = one_matrix(rows, cols, d_bitmap, reinterpret_cast<const uint16_t *>(d_values), nnz,
+                                      reinterpret_cast<uint16_t *>(d_dense));
+    return run_batch(&m, 1, const_cast<void *>(d_workspace), workspace_bytes, stream, false, true, 1);
+}
+
+extern "C" endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, int count, void *d_workspace,
+                                                  size_t workspace_bytes, void *stream) {
+    return run_batch(reinterpret_cast<const endor_matrix *>(mats), count, d_workspace, workspace_bytes, stream,
+                     true, true, 1);
 }

@@ -281,3 +281,76 @@ def test_h2d_pipeline_row_blocks_matches_oracle(shape, nblocks):
     torch.cuda.synchronize()
     expect = orc.decompress(rows, cols, c.bitmap, c.values)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), expect) and np.array_equal(expect, w)
+
+
+# ---------------------------------------------------------------------------
+# 8-bit elements (Section 4.2): same bitmap, one byte per value
+# ---------------------------------------------------------------------------
+def _random_compressed_u8(rows, cols, keep, seed):
+    n = rows * cols
+    g = np.random.default_rng(seed)
+    bits = g.random(n) < keep
+    bitmap = np.zeros(endor.bitmap_bytes(rows, cols), np.uint8)
+    packed = np.packbits(bits, bitorder="little")
+    bitmap[: packed.size] = packed
+    values = g.integers(0, 256, size=int(bits.sum()), dtype=np.uint16).astype(np.uint8)   # zero bytes allowed
+    return endor.Compressed(rows, cols, bitmap, values, None)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.1, 0.5, 0.9, 1.0])
+def test_decompress_u8_matches_oracle(shape, keep):
+    rows, cols = shape
+    _say(f"u8 case shape={shape} keep={keep}")
+    c = _random_compressed_u8(rows, cols, keep, seed=rows * 17 + cols)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    assert expect.dtype == np.uint8
+    m = endor.to_device(c)
+    out = torch.full((rows, cols), 0xA5, dtype=torch.uint8, device="cuda")
+    endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), expect)
+
+
+@pytest.mark.parametrize("voff", [1, 5, 15])
+@pytest.mark.parametrize("ooff", [0, 1, 8])
+def test_u8_unaligned_values_and_output(voff, ooff):
+    rows, cols = 9, 5000
+    n = rows * cols
+    c = _random_compressed_u8(rows, cols, 0.5, seed=voff * 10 + ooff)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values).reshape(-1)
+    bm = torch.from_numpy(c.bitmap).cuda()
+    vbuf = torch.full((voff + c.nnz + 17,), 0x55, dtype=torch.uint8, device="cuda")
+    vbuf[voff:voff + c.nnz] = torch.from_numpy(c.values).cuda()
+    m = endor.DeviceMatrix(rows, cols, bm, vbuf[voff:voff + c.nnz], c.nnz)
+    obuf = torch.full((ooff + n + 32,), 0xA5, dtype=torch.uint8, device="cuda")
+    endor.decompress(m, out=obuf[ooff:ooff + n])
+    torch.cuda.synchronize()
+    host = obuf.cpu().numpy()
+    assert np.array_equal(host[ooff:ooff + n], expect)
+    assert np.all(host[:ooff] == 0xA5) and np.all(host[ooff + n:] == 0xA5)
+
+
+def test_u8_batch_and_table_reuse_full_size():
+    """The paper's 8-bit example shape (9216 x 36864, half kept) plus its transpose shape, batched."""
+    _say("u8 full size")
+    cs, dense = [], []
+    for i, (rows, cols) in enumerate([(9216, 36864), (36864, 9216)]):
+        w = synth.pruned_int8(rows, cols, 0.5, seed=synth.seed_for(2, i, 8))
+        cs.append(endor.compress(w, want_row_offsets=False))
+        dense.append(w)
+    c0 = cs[0]
+    # size law of Section 4.2 on real buffers: 1/8 + nnz/N of the dense size (62 % printed for one half kept)
+    ratio = (c0.rows * c0.cols // 8 + c0.nnz) / (c0.rows * c0.cols)
+    assert abs(ratio - 0.625) < 1e-3
+    mats = [endor.to_device(c) for c in cs]
+    outs = [torch.full((c.rows, c.cols), 0xA5, dtype=torch.uint8, device="cuda") for c in cs]
+    _, ws = endor.decompress_batch(mats, outs=outs)
+    torch.cuda.synchronize()
+    for c, w, o in zip(cs, dense, outs):
+        expect = orc.decompress(c.rows, c.cols, c.bitmap, c.values)
+        assert np.array_equal(expect, w)
+        assert np.array_equal(o.cpu().numpy(), expect)
+    again = endor.decompress_with_offsets(mats[0], ws)   # matrix 0's table sits at the start of the batch workspace
+    torch.cuda.synchronize()
+    assert torch.equal(again, outs[0])

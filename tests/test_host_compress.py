@@ -84,3 +84,21 @@ def test_compress_error_paths():
     assert call(None, 4, 0, None, None, 0, ro.ctypes.data, ctypes.byref(nnz)) == 0
     assert nnz.value == 0 and not ro.any()
     assert L.endor_status_string(2) == b"buffer too small"
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.5, 1.0])
+def test_compress_u8_matches_oracle(shape, keep):
+    """8-bit elements (Section 4.2): same bitmap, one byte per value."""
+    rows, cols = shape
+    g = np.random.default_rng(rows * 11 + cols)
+    w = g.integers(1, 256, size=(rows, cols), dtype=np.uint16).astype(np.uint8)
+    w[g.random((rows, cols)) >= keep] = 0
+    c = endor.compress(w)
+    b, v, r = orc.compress(w)
+    assert c.values.dtype == np.uint8
+    assert np.array_equal(c.bitmap, _oracle_bitmap_padded(rows, cols, b))
+    assert np.array_equal(c.values, v)
+    assert np.array_equal(c.row_offsets, r)
+    # compressed size of the 8-bit variant: N/8 + nnz bytes
+    assert b.nbytes + c.values.nbytes == (rows * cols + 7) // 8 + int(np.count_nonzero(w))
