@@ -196,6 +196,28 @@ endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, int count,
                                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * DEVICE.  Row-subset decompression: the selective load that Section 4.2 sketches for
+ * activation sparsity (only the rows of an up-projection whose neurons are predicted
+ * active are needed).  Output row r (of nsel) is row d_sel[r] of the matrix; the values
+ * of a row start at d_row_offsets[row], the per-row table that endor_compress emits on
+ * the host (copy it to the device) or endor_build_offsets builds on the device.
+ * d_sel and d_row_offsets are device arrays of int64.  Rows may repeat and come in any
+ * order.  An index outside [0, rows) leaves its output row untouched.  No workspace.
+ * d_out: nsel*cols elements; 16-byte alignment with a row pitch that is a multiple of
+ * 16 bytes selects the fast store path.  nsel*cols must be below 2^34.
+ */
+endor_status endor_decompress_rows(int64_t rows, int64_t cols,
+                                   const uint8_t *d_bitmap, const uint16_t *d_values, int64_t nnz,
+                                   const int64_t *d_row_offsets,
+                                   const int64_t *d_sel, int64_t nsel,
+                                   uint16_t *d_out, void *stream);
+endor_status endor_decompress_rows_u8(int64_t rows, int64_t cols,
+                                      const uint8_t *d_bitmap, const uint8_t *d_values, int64_t nnz,
+                                      const int64_t *d_row_offsets,
+                                      const int64_t *d_sel, int64_t nsel,
+                                      uint8_t *d_out, void *stream);
+
+/*
  * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
  * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
  * is copied from host memory to GPU memory and decompressed there; Section 6 notes

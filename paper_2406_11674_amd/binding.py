@@ -18,7 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
-    "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
+    "decompress_rows", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
+        for name in ("endor_decompress_rows", "endor_decompress_rows_u8"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _i64, _p, _p]
         L.endor_stage_bytes.restype = _sz
         L.endor_stage_bytes.argtypes = [_i64, _i64, _i64]
         L.endor_h2d_decompress_pipeline.restype = ctypes.c_int
@@ -278,6 +282,20 @@ def decompress_batch_with_offsets(mats, workspace, outs=None, stream=None):
         outs = [_new_dense(m.rows, m.cols, mats[0].bitmap.device) for m in mats]
     _batch("endor_decompress_batch_with_offsets", mats, outs, workspace, stream)
     return outs
+
+
+def decompress_rows(m: DeviceMatrix, row_offsets, sel, out=None, stream=None):
+    """endor_decompress_rows[_u8]: out[r] = row sel[r].  row_offsets, sel: int64 device tensors."""
+    torch = _torch()
+    if row_offsets.dtype != torch.int64 or sel.dtype != torch.int64:
+        raise ValueError("row_offsets and sel must be int64 tensors")
+    nsel = int(sel.numel())
+    if out is None:
+        out = _new_dense(nsel, m.cols, m.bitmap.device, m.elem_bytes)
+    fn = lib().endor_decompress_rows if m.elem_bytes == 2 else lib().endor_decompress_rows_u8
+    _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets), _dptr(sel),
+              nsel, _dptr(out), _stream_handle(stream)), "endor_decompress_rows")
+    return out
 
 
 # ------------------------------------------------------------------ host -> device pipeline

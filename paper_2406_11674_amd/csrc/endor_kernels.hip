@@ -409,6 +409,76 @@ __global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams 
     }
 }
 
+// ---------------------------------------------------------------- kernel 2b: selected rows
+
+struct RowsParams {
+    const uint64_t *bitmap;
+    const void *values;
+    void *out;                   // nsel x cols
+    const int64_t *row_offsets;  // rows + 1
+    const int64_t *sel;          // nsel row indices
+    int64_t rows, cols, nnz, nsel;
+    uint32_t segs;               // ceil(cols / 4096) tiles per row
+};
+
+// Row-subset decompression (the selective load of Section 4.2): output row r is row
+// sel[r] of the matrix.  One wave per (selected row, 4096-column segment).  The segment
+// starts at an arbitrary bit position, so a lane's 64 bits are funnelled out of two
+// neighbouring bitmap words; its first value is row_offsets[row] plus the 1 bits of the
+// row's earlier segments, counted here from the bitmap.
+template <int E, bool kAlignedOut>
+__global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
+    __shared__ WaveScratch<E> s_scratch;
+    const uint32_t lane = threadIdx.x;
+    const int64_t r = blockIdx.x / R.segs;
+    const uint32_t g = blockIdx.x % R.segs;
+    const int64_t i = R.sel[r];
+    if (i < 0 || i >= R.rows) return;  // an index outside the matrix leaves its output row untouched
+
+    const int64_t n = R.rows * R.cols;
+    const int64_t nwords = (n + 63) >> 6;
+    const int64_t row_bit = i * R.cols;                  // first bit of the row
+    const int64_t e = row_bit + int64_t(g) * kTileElems;  // first bit of the segment
+    const int64_t left = R.cols - int64_t(g) * kTileElems;
+    const uint32_t nbits = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+
+    // 1 bits of the row before this segment: words [row_bit>>6, e>>6], first and last partial
+    uint32_t before = 0;
+    {
+        const int64_t wa = row_bit >> 6, wb = e >> 6;
+        for (int64_t w = wa + lane; w <= wb; w += 64) {
+            uint64_t x = w < nwords ? R.bitmap[w] : 0;
+            if (w == wa) x &= ~uint64_t(0) << (row_bit & 63);
+            if (w == wb) x &= (uint64_t(1) << (e & 63)) - 1;
+            before += __popcll(x);
+        }
+        before = wave_sum(before);
+    }
+
+    // this lane's 64 bits of the segment, taken from bit position e + 64*lane
+    const int64_t w0 = (e >> 6) + lane;
+    const uint32_t bs = static_cast<uint32_t>(e & 63);
+    uint64_t word = 0;
+    if (lane * 64 < nbits) {
+        const uint64_t lo = w0 < nwords ? R.bitmap[w0] : 0;
+        word = lo >> bs;
+        if (bs != 0) {
+            const uint64_t hi = w0 + 1 < nwords ? R.bitmap[w0 + 1] : 0;
+            word |= hi << (64 - bs);
+        }
+        const uint32_t rem = nbits - lane * 64;  // bits of this lane that belong to the segment
+        if (rem < 64) word &= (uint64_t(1) << rem) - 1;
+    }
+    const uint32_t cnt = wave_sum(__popcll(word));
+
+    const uintptr_t vbeg = reinterpret_cast<uintptr_t>(R.values);
+    const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(R.nnz);
+    const uint64_t first = static_cast<uint64_t>(R.row_offsets[i]) + before;
+    expand_tile<E, kAlignedOut>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend,
+                                reinterpret_cast<uint8_t *>(R.out) + (r * R.cols + int64_t(g) * kTileElems) * E,
+                                nbits);
+}
+
 // ---------------------------------------------------------------- kernel 3: row offsets
 
 // One wave per row start: rank(i*cols) = chunk start + tile offset + 1 bits of the
@@ -677,4 +747,70 @@ extern "C" endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, i
                                                   size_t workspace_bytes, void *stream) {
     return run_batch(reinterpret_cast<const endor_matrix *>(mats), count, d_workspace, workspace_bytes, stream,
                      true, true, 1);
+}
+
+// ---------------------------------------------------------------- selected rows (Section 4.2)
+
+namespace {
+
+endor_status run_rows(int elem_bytes, int64_t rows, int64_t cols, const uint8_t *d_bitmap, const void *d_values,
+                      int64_t nnz, const int64_t *d_row_offsets, const int64_t *d_sel, int64_t nsel, void *d_out,
+                      void *stream) {
+    if (rows < 0 || cols < 0 || nsel < 0 || nnz < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    if (nsel == 0 || cols == 0) return ENDOR_OK;
+    if (nsel > kMaxElems / cols) return ENDOR_ERR_UNSUPPORTED;
+    const uintptr_t em = static_cast<uintptr_t>(elem_bytes - 1);
+    if (nnz > rows * cols) return ENDOR_ERR_INVALID_ARG;
+    if (!d_bitmap || (reinterpret_cast<uintptr_t>(d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (nnz > 0 && (!d_values || (reinterpret_cast<uintptr_t>(d_values) & em))) return ENDOR_ERR_INVALID_ARG;
+    if (!d_row_offsets || (reinterpret_cast<uintptr_t>(d_row_offsets) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (!d_sel || (reinterpret_cast<uintptr_t>(d_sel) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & em)) return ENDOR_ERR_INVALID_ARG;
+    RowsParams R;
+    R.bitmap = reinterpret_cast<const uint64_t *>(d_bitmap);
+    R.values = d_values;
+    R.out = d_out;
+    R.row_offsets = d_row_offsets;
+    R.sel = d_sel;
+    R.rows = rows;
+    R.cols = cols;
+    R.nnz = nnz;
+    R.nsel = nsel;
+    R.segs = static_cast<uint32_t>((cols + kTileElems - 1) / kTileElems);
+    const int64_t blocks = nsel * R.segs;
+    if (blocks > 0x7fffffff) return ENDOR_ERR_UNSUPPORTED;
+    // every segment start (r*cols + g*4096 elements) is 16-byte aligned iff the row pitch is
+    const bool aligned = (reinterpret_cast<uintptr_t>(d_out) & 15) == 0 && (cols * elem_bytes) % 16 == 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(static_cast<unsigned>(blocks));
+    if (elem_bytes == 2) {
+        if (aligned)
+            hipLaunchKernelGGL((endor_expand_rows_kernel<2, true>), grid, dim3(64), 0, s, R);
+        else
+            hipLaunchKernelGGL((endor_expand_rows_kernel<2, false>), grid, dim3(64), 0, s, R);
+    } else {
+        if (aligned)
+            hipLaunchKernelGGL((endor_expand_rows_kernel<1, true>), grid, dim3(64), 0, s, R);
+        else
+            hipLaunchKernelGGL((endor_expand_rows_kernel<1, false>), grid, dim3(64), 0, s, R);
+    }
+    if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    return ENDOR_OK;
+}
+
+}  // namespace
+
+extern "C" endor_status endor_decompress_rows(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                              const uint16_t *d_values, int64_t nnz,
+                                              const int64_t *d_row_offsets, const int64_t *d_sel, int64_t nsel,
+                                              uint16_t *d_out, void *stream) {
+    return run_rows(2, rows, cols, d_bitmap, d_values, nnz, d_row_offsets, d_sel, nsel, d_out, stream);
+}
+
+extern "C" endor_status endor_decompress_rows_u8(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                                 const uint8_t *d_values, int64_t nnz,
+                                                 const int64_t *d_row_offsets, const int64_t *d_sel,
+                                                 int64_t nsel, uint8_t *d_out, void *stream) {
+    return run_rows(1, rows, cols, d_bitmap, d_values, nnz, d_row_offsets, d_sel, nsel, d_out, stream);
 }

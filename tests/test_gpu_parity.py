@@ -354,3 +354,78 @@ def test_u8_batch_and_table_reuse_full_size():
     again = endor.decompress_with_offsets(mats[0], ws)   # matrix 0's table sits at the start of the batch workspace
     torch.cuda.synchronize()
     assert torch.equal(again, outs[0])
+
+
+# ---------------------------------------------------------------------------
+# row-subset decompression (the selective load of Section 4.2)
+# ---------------------------------------------------------------------------
+ROW_SHAPES = [(40, 77), (5, 3), (64, 64), (33, 4096), (17, 4097), (9, 12345), (300, 8192), (50, 28672), (7, 28673)]
+
+
+@pytest.mark.parametrize("shape", ROW_SHAPES, ids=str)
+@pytest.mark.parametrize("wide", [True, False], ids=["fp16", "u8"])
+def test_decompress_rows_matches_oracle(shape, wide):
+    rows, cols = shape
+    _say(f"rows case shape={shape} wide={wide}")
+    if wide:
+        w = synth.pruned_fp16(rows, cols, 0.5, seed=rows + cols, row_skew=True)
+    else:
+        w = synth.pruned_int8(rows, cols, 0.4, seed=rows + cols)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    g = np.random.default_rng(rows)
+    sel_np = np.concatenate([g.integers(0, rows, size=max(1, rows // 2)), [rows - 1, 0, 0]]).astype(np.int64)
+    sel = torch.from_numpy(sel_np).cuda()
+    ro_host = torch.from_numpy(c.row_offsets).cuda()
+    _, ro_dev = endor.build_offsets(m, row_offsets=True)
+    expect = orc.decompress_selected_rows(cols, sel_np, c.row_offsets, c.bitmap, c.values)
+    assert np.array_equal(expect, w.view(expect.dtype)[sel_np])          # the oracle's own pin, on this input
+    for ro in (ro_host, ro_dev):
+        out = torch.full((sel_np.size, cols), 0x5A, dtype=torch.int16 if wide else torch.uint8, device="cuda")
+        endor.decompress_rows(m, ro, sel, out=out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(expect.dtype), expect)
+
+
+def test_decompress_rows_out_of_range_index_is_skipped():
+    rows, cols = 12, 5000
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=77)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    sel_np = np.array([3, -1, rows, 11], np.int64)
+    out = torch.full((4, cols), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress_rows(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda(), out=out)
+    torch.cuda.synchronize()
+    host = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(host[0], w[3]) and np.array_equal(host[3], w[11])
+    assert np.all(host[1] == POISON) and np.all(host[2] == POISON)
+
+
+def test_decompress_rows_unaligned_output():
+    rows, cols = 20, 4099   # odd row pitch: every output row starts 2-byte aligned only
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=78)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    sel_np = np.arange(rows - 1, -1, -1, dtype=np.int64)
+    buf = torch.full((1 + rows * cols + 8,), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress_rows(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda(),
+                          out=buf[1:1 + rows * cols])
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint16)
+    assert np.array_equal(host[1:1 + rows * cols].reshape(rows, cols), w[sel_np])
+    assert host[0] == POISON and np.all(host[1 + rows * cols:] == POISON)
+
+
+def test_decompress_rows_full_size_gate_proj():
+    """A tenth of the rows of a Llama2-70B gate projection (28672 x 8192)."""
+    rows, cols = 28672, 8192
+    _say("rows full size")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=synth.seed_for(3, 4))
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    sel_np = np.sort(np.random.default_rng(5).choice(rows, size=rows // 10, replace=False)).astype(np.int64)
+    out = endor.decompress_rows(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda())
+    torch.cuda.synchronize()
+    expect = orc.decompress_selected_rows(cols, sel_np, c.row_offsets, c.bitmap, c.values)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), expect)
+    assert np.array_equal(expect, w[sel_np])
