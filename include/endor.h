@@ -218,6 +218,27 @@ endor_status endor_decompress_rows_u8(int64_t rows, int64_t cols,
                                       uint8_t *d_out, void *stream);
 
 /*
+ * DEVICE.  Algorithm 1 on the GPU (the paper runs it on the host, before inference;
+ * Section 4.1 "Compression"): d_dense (rows*cols elements, device) is turned into
+ * d_bitmap (endor_bitmap_bytes, fully written, pad bits zero) and d_values (packed
+ * non-zeros in row-major order).  The number of non-zeros is only known on the device:
+ * it is written to *d_nnz_out (device int64, required), and no value is ever written at
+ * or past values_capacity, so a caller that cannot bound nnz runs with capacity 0 first
+ * (bitmap, offsets and *d_nnz_out are still produced) or passes capacity rows*cols.
+ * d_row_offsets (device, rows+1 entries) is optional.  Afterwards d_workspace holds the
+ * tile offset table of the new bitmap, ready for the *_with_offsets entry points.
+ * Alignment as elsewhere; a 16-byte aligned d_dense selects the fast load path.
+ */
+endor_status endor_compress_device(int64_t rows, int64_t cols, const uint16_t *d_dense,
+                                   uint8_t *d_bitmap, uint16_t *d_values, int64_t values_capacity,
+                                   void *d_workspace, size_t workspace_bytes,
+                                   int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream);
+endor_status endor_compress_device_u8(int64_t rows, int64_t cols, const uint8_t *d_dense,
+                                      uint8_t *d_bitmap, uint8_t *d_values, int64_t values_capacity,
+                                      void *d_workspace, size_t workspace_bytes,
+                                      int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream);
+
+/*
  * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
  * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
  * is copied from host memory to GPU memory and decompressed there; Section 6 notes

@@ -18,7 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
-    "decompress_rows", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
+    "decompress_rows", "compress_device", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
@@ -85,6 +85,10 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _i64, _p, _p]
+        for name in ("endor_compress_device", "endor_compress_device_u8"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [_i64, _i64, _p, _p, _p, _i64, _p, _sz, _p, _p, _p]
         L.endor_stage_bytes.restype = _sz
         L.endor_stage_bytes.argtypes = [_i64, _i64, _i64]
         L.endor_h2d_decompress_pipeline.restype = ctypes.c_int
@@ -296,6 +300,32 @@ def decompress_rows(m: DeviceMatrix, row_offsets, sel, out=None, stream=None):
     _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets), _dptr(sel),
               nsel, _dptr(out), _stream_handle(stream)), "endor_decompress_rows")
     return out
+
+
+def compress_device(dense, values=None, row_offsets: bool = False, stream=None):
+    """endor_compress_device[_u8] on a 2-d device tensor of 2- or 1-byte elements.
+    Returns (DeviceMatrix, workspace, row_offsets or None).  `values`: preallocated
+    buffer (its length is the capacity); default rows*cols elements.  Synchronises once
+    to read the number of non-zeros back."""
+    torch = _torch()
+    rows, cols = dense.shape
+    eb = dense.element_size()
+    if eb not in (1, 2) or not dense.is_contiguous():
+        raise ValueError("dense must be a contiguous 2-d tensor of 1- or 2-byte elements")
+    dev = dense.device
+    bitmap = torch.empty(bitmap_bytes(rows, cols), dtype=torch.uint8, device=dev)
+    if values is None:
+        values = torch.empty(rows * cols, dtype=torch.int16 if eb == 2 else torch.uint8, device=dev)
+    ws = _new_workspace(workspace_bytes(rows, cols), dev)
+    ro = torch.empty(rows + 1, dtype=torch.int64, device=dev) if row_offsets else None
+    nnz = torch.zeros(1, dtype=torch.int64, device=dev)
+    fn = lib().endor_compress_device if eb == 2 else lib().endor_compress_device_u8
+    _check(fn(rows, cols, _dptr(dense), _dptr(bitmap), _dptr(values), values.numel(), _dptr(ws), ws.numel(),
+              _dptr(ro), _dptr(nnz), _stream_handle(stream)), "endor_compress_device")
+    n = int(nnz.item())
+    if n > values.numel():
+        raise EndorError(2, f"endor_compress_device: {n} non-zeros, capacity {values.numel()}")
+    return DeviceMatrix(rows, cols, bitmap, values[:n], n), ws, ro
 
 
 # ------------------------------------------------------------------ host -> device pipeline

@@ -479,6 +479,190 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
                                 nbits);
 }
 
+// ---------------------------------------------------------------- device-side compression
+
+// 16 bytes of the dense matrix: elements [le, le + kLaneElems) of a tile that has
+// `nvalid` elements; elements past the end read as zero.
+template <int E, bool kAlignedIn>
+__device__ __forceinline__ u32x4 load_dense16(const uint8_t *tile_in, uint32_t le, uint32_t nvalid) {
+    if (kAlignedIn && le + Shape<E>::kLaneElems <= nvalid)
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(tile_in + size_t(le) * E));
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < Shape<E>::kLaneElems; ++j) {
+        uint32_t v = 0;
+        if (le + j < nvalid)
+            v = (E == 2) ? uint32_t(reinterpret_cast<const uint16_t *>(tile_in)[le + j]) : uint32_t(tile_in[le + j]);
+        d[(E * j) >> 2] |= v << (8 * ((E * j) & 3));
+    }
+    u32x4 r;
+    r.x = d[0];
+    r.y = d[1];
+    r.z = d[2];
+    r.w = d[3];
+    return r;
+}
+
+// bit j = (element j of the 16 bytes is not the all-zero pattern)
+template <int E>
+__device__ __forceinline__ uint32_t nonzero_bits(u32x4 d) {
+    const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < Shape<E>::kLaneElems; ++j) {
+        const uint32_t v = (dd[(E * j) >> 2] >> (8 * ((E * j) & 3))) & ((E == 2) ? 0xffffu : 0xffu);
+        bits |= (v != 0 ? 1u : 0u) << j;
+    }
+    return bits;
+}
+
+struct CompressParams {
+    const void *dense;
+    uint64_t *bitmap;
+    void *values;
+    int64_t n;
+    int64_t capacity;  // elements `values` has room for
+    MatParams table;   // chunk_total / tile_off of this matrix (bitmap, n filled in as well)
+};
+
+// Algorithm 1, step 1 on the device: the position bitmap.  One wave per tile; the lane
+// bit groups of the 4096 elements are assembled into 64-bit words through LDS.
+template <int E, bool kAlignedIn>
+__global__ __launch_bounds__(64) void endor_mask_kernel(CompressParams C) {
+    using Sh = Shape<E>;
+    __shared__ uint64_t s_words[kTileWords];
+    const uint32_t lane = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const int64_t e0 = tile * kTileElems;
+    const int64_t left = C.n - e0;
+    const uint32_t nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+    const uint8_t *tile_in = reinterpret_cast<const uint8_t *>(C.dense) + e0 * E;
+    u32x4 d[Sh::kSteps];
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) d[k] = load_dense16<E, kAlignedIn>(tile_in, (k * 64 + lane) * Sh::kLaneElems, nvalid);
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) {
+        const uint32_t bits = nonzero_bits<E>(d[k]);
+        if (E == 2)
+            reinterpret_cast<uint8_t *>(s_words)[k * 64 + lane] = static_cast<uint8_t>(bits);
+        else
+            reinterpret_cast<uint16_t *>(s_words)[k * 64 + lane] = static_cast<uint16_t>(bits);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int64_t w = tile * kTileWords + lane;
+    if (w < ((C.n + 63) >> 6)) C.bitmap[w] = s_words[lane];  // pad bits are zero: elements past n read as zero
+}
+
+// Algorithm 1, step 2 on the device: pack the non-zero elements of one tile at the
+// tile's offset.  The values are scattered into LDS at rank order and written out in
+// 16-byte units; the units a tile shares with its neighbours (first and last) are
+// written element by element so that each element of `values` has exactly one writer.
+template <int E, bool kAlignedIn>
+__global__ __launch_bounds__(64) void endor_pack_kernel(CompressParams C) {
+    using Sh = Shape<E>;
+    __shared__ WaveScratch<E> S;
+    const uint32_t lane = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const MatParams &M = C.table;
+    const uint32_t c = static_cast<uint32_t>(tile / kTilesPerChunk);
+    const uint32_t tl = static_cast<uint32_t>(tile % kTilesPerChunk);
+    const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl;
+    const uint32_t o0 = tile_off[0];
+    uint32_t cnt = tile_off[1] - o0;
+    cnt = cnt > kTileElems ? kTileElems : cnt;
+    const uint64_t first = chunk_base(M.chunk_total, c, lane) + o0;  // index of the tile's first value
+
+    const int64_t e0 = tile * kTileElems;
+    const int64_t left = C.n - e0;
+    const uint32_t nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+    const uint8_t *tile_in = reinterpret_cast<const uint8_t *>(C.dense) + e0 * E;
+    u32x4 d[Sh::kSteps];
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) d[k] = load_dense16<E, kAlignedIn>(tile_in, (k * 64 + lane) * Sh::kLaneElems, nvalid);
+
+    const uintptr_t vbase = reinterpret_cast<uintptr_t>(C.values);
+    const uintptr_t vaddr = vbase + E * first;
+    const uintptr_t a16 = vaddr & ~uintptr_t(15);
+    const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;
+
+    // word popcounts from the data itself (the same bits endor_mask_kernel wrote)
+    uint32_t bits[Sh::kSteps];
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) {
+        bits[k] = nonzero_bits<E>(d[k]);
+        if (E == 2)
+            reinterpret_cast<uint8_t *>(S.words)[k * 64 + lane] = static_cast<uint8_t>(bits[k]);
+        else
+            reinterpret_cast<uint16_t *>(S.words)[k * 64 + lane] = static_cast<uint16_t>(bits[k]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint64_t word = S.words[lane];
+    const uint32_t pc = __popcll(word);
+    const uint32_t incl = wave_inclusive_scan(pc);
+    S.start[lane] = incl - pc + shift;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // scatter the non-zero elements into LDS in rank order
+#pragma unroll
+    for (int k = 0; k < Sh::kSteps; ++k) {
+        const uint32_t wi = k * Sh::kLaneElems + lane / Sh::kLanesPerWord;
+        const uint64_t w = S.words[wi];
+        const uint32_t sh = (lane % Sh::kLanesPerWord) * Sh::kLaneElems;
+        const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
+        const uint32_t dd[4] = {d[k].x, d[k].y, d[k].z, d[k].w};
+#pragma unroll
+        for (int j = 0; j < Sh::kLaneElems; ++j) {
+            if ((bits[k] >> j) & 1u) {
+                const uint32_t idx = s + __popc(bits[k] & ((1u << j) - 1));
+                const uint32_t v = dd[(E * j) >> 2] >> (8 * ((E * j) & 3));
+                if (E == 2)
+                    reinterpret_cast<uint16_t *>(S.stage)[idx] = static_cast<uint16_t>(v);
+                else
+                    reinterpret_cast<uint8_t *>(S.stage)[idx] = static_cast<uint8_t>(v);
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // write the slice out: elements [shift, shift + cnt) of the staging area go to
+    // values[first, first + cnt), never past `capacity`
+    const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;
+    const int64_t room = C.capacity - static_cast<int64_t>(first);  // elements this tile may write
+    for (uint32_t ch = lane; ch < nch; ch += 64) {
+        const uint32_t el0 = ch * Sh::kLaneElems;  // staging index of the unit's first element
+        const bool inside = el0 >= shift && el0 + Sh::kLaneElems <= shift + cnt &&
+                            static_cast<int64_t>(el0 + Sh::kLaneElems - shift) <= room;
+        if (inside) {
+            *reinterpret_cast<u32x4 *>(a16 + 16 * uintptr_t(ch)) = S.stage[ch];
+        } else {
+#pragma unroll
+            for (int j = 0; j < Sh::kLaneElems; ++j) {
+                const uint32_t el = el0 + j;
+                if (el >= shift && el < shift + cnt && static_cast<int64_t>(el - shift) < room) {
+                    if (E == 2)
+                        reinterpret_cast<uint16_t *>(a16)[el] = reinterpret_cast<const uint16_t *>(S.stage)[el];
+                    else
+                        reinterpret_cast<uint8_t *>(a16)[el] = reinterpret_cast<const uint8_t *>(S.stage)[el];
+                }
+            }
+        }
+    }
+}
+
+// total number of 1 bits of a matrix whose table has been built: one wave
+__global__ __launch_bounds__(64) void endor_total_kernel(MatParams M, int64_t *__restrict__ nnz_out) {
+    const uint64_t total = chunk_base(M.chunk_total, M.nchunks, threadIdx.x);
+    if (threadIdx.x == 0) *nnz_out = static_cast<int64_t>(total);
+}
+
 // ---------------------------------------------------------------- kernel 3: row offsets
 
 // One wave per row start: rank(i*cols) = chunk start + tile offset + 1 bits of the
@@ -813,4 +997,82 @@ extern "C" endor_status endor_decompress_rows_u8(int64_t rows, int64_t cols, con
                                                  const int64_t *d_row_offsets, const int64_t *d_sel,
                                                  int64_t nsel, uint8_t *d_out, void *stream) {
     return run_rows(1, rows, cols, d_bitmap, d_values, nnz, d_row_offsets, d_sel, nsel, d_out, stream);
+}
+
+// ---------------------------------------------------------------- device-side compression
+
+namespace {
+
+template <int E>
+endor_status run_compress_device(int64_t rows, int64_t cols, const void *d_dense, uint8_t *d_bitmap,
+                                 void *d_values, int64_t values_capacity, void *d_workspace,
+                                 size_t workspace_bytes, int64_t *d_row_offsets, int64_t *d_nnz_out,
+                                 void *stream) {
+    if (rows < 0 || cols < 0 || values_capacity < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    if (!d_nnz_out || (reinterpret_cast<uintptr_t>(d_nnz_out) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (d_row_offsets && (reinterpret_cast<uintptr_t>(d_row_offsets) & 7)) return ENDOR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t n = rows * cols;
+    const uintptr_t em = E - 1;
+    if (n > 0) {
+        if (!d_dense || (reinterpret_cast<uintptr_t>(d_dense) & em)) return ENDOR_ERR_INVALID_ARG;
+        if (!d_bitmap || (reinterpret_cast<uintptr_t>(d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
+        if (values_capacity > 0 && (!d_values || (reinterpret_cast<uintptr_t>(d_values) & em)))
+            return ENDOR_ERR_INVALID_ARG;
+        if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255)) return ENDOR_ERR_INVALID_ARG;
+        if (workspace_bytes < workspace_bytes_n(n)) return ENDOR_ERR_BUFFER_TOO_SMALL;
+    }
+    // the table (and the row offsets) come from the ordinary offsets path, run on the
+    // bitmap the mask kernel writes
+    CompressParams C{};
+    C.dense = d_dense;
+    C.bitmap = reinterpret_cast<uint64_t *>(d_bitmap);
+    C.values = d_values;
+    C.n = n;
+    C.capacity = values_capacity;
+    const bool aligned_in = (reinterpret_cast<uintptr_t>(d_dense) & 15) == 0;
+    const unsigned ntiles = static_cast<unsigned>((n + kTileElems - 1) / kTileElems);
+    if (n > 0) {
+        if (aligned_in)
+            hipLaunchKernelGGL((endor_mask_kernel<E, true>), dim3(ntiles), dim3(64), 0, s, C);
+        else
+            hipLaunchKernelGGL((endor_mask_kernel<E, false>), dim3(ntiles), dim3(64), 0, s, C);
+        if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    }
+    endor_status st = endor_build_offsets(rows, cols, d_bitmap, d_workspace, workspace_bytes, d_row_offsets, stream);
+    if (st != ENDOR_OK) return st;
+    if (n > 0) {
+        const endor_matrix m = one_matrix(rows, cols, d_bitmap, nullptr, 0, nullptr);
+        size_t off = 0;
+        Group g;
+        fill_group(&m, 1, kNeedBitmap, E, static_cast<char *>(d_workspace), workspace_bytes, &off, &g);
+        C.table = g.P.m[0];
+        if (aligned_in)
+            hipLaunchKernelGGL((endor_pack_kernel<E, true>), dim3(ntiles), dim3(64), 0, s, C);
+        else
+            hipLaunchKernelGGL((endor_pack_kernel<E, false>), dim3(ntiles), dim3(64), 0, s, C);
+        if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    }
+    hipLaunchKernelGGL(endor_total_kernel, dim3(1), dim3(64), 0, s, C.table, d_nnz_out);
+    if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    return ENDOR_OK;
+}
+
+}  // namespace
+
+extern "C" endor_status endor_compress_device(int64_t rows, int64_t cols, const uint16_t *d_dense,
+                                              uint8_t *d_bitmap, uint16_t *d_values, int64_t values_capacity,
+                                              void *d_workspace, size_t workspace_bytes,
+                                              int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream) {
+    return run_compress_device<2>(rows, cols, d_dense, d_bitmap, d_values, values_capacity, d_workspace,
+                                  workspace_bytes, d_row_offsets, d_nnz_out, stream);
+}
+
+extern "C" endor_status endor_compress_device_u8(int64_t rows, int64_t cols, const uint8_t *d_dense,
+                                                 uint8_t *d_bitmap, uint8_t *d_values, int64_t values_capacity,
+                                                 void *d_workspace, size_t workspace_bytes,
+                                                 int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream) {
+    return run_compress_device<1>(rows, cols, d_dense, d_bitmap, d_values, values_capacity, d_workspace,
+                                  workspace_bytes, d_row_offsets, d_nnz_out, stream);
 }

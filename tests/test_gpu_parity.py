@@ -429,3 +429,81 @@ def test_decompress_rows_full_size_gate_proj():
     expect = orc.decompress_selected_rows(cols, sel_np, c.row_offsets, c.bitmap, c.values)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), expect)
     assert np.array_equal(expect, w[sel_np])
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 on the device (endor_compress_device) against the oracle's Algorithm 1
+# ---------------------------------------------------------------------------
+def _check_device_compress(w):
+    rows, cols = w.shape
+    dense = torch.from_numpy(w.view(np.int16) if w.dtype.itemsize == 2 else w).cuda()
+    m, ws, ro = endor.compress_device(dense, row_offsets=True)
+    torch.cuda.synchronize()
+    b, v, r = orc.compress(w)
+    bm = m.bitmap.cpu().numpy()
+    assert np.array_equal(bm[: b.size], b) and not bm[b.size:].any()      # pad bits/bytes are zero
+    assert m.nnz == v.size
+    assert np.array_equal(m.values.cpu().numpy().view(v.dtype), v)
+    assert np.array_equal(ro.cpu().numpy(), r)
+    # and the table it leaves behind serves decompression: device round trip
+    back = endor.decompress_with_offsets(m, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().view(w.dtype), w)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=str)
+@pytest.mark.parametrize("keep", [0.0, 0.5, 1.0])
+def test_compress_device_matches_oracle(shape, keep):
+    rows, cols = shape
+    _say(f"device compress shape={shape} keep={keep}")
+    g = np.random.default_rng(rows * 3 + cols)
+    w = g.integers(1, 1 << 16, size=(rows, cols), dtype=np.uint32).astype(np.uint16)
+    w[g.random((rows, cols)) >= keep] = 0
+    if w.size > 6:
+        w.reshape(-1)[[1, 3, 5]] = [0x8000, 0x0001, 0x7E01]     # -0.0, subnormal, NaN are values
+    _check_device_compress(w)
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 5), (1, 4097), (33, 4099), (1031, 2053)], ids=str)
+def test_compress_device_u8_matches_oracle(shape):
+    _check_device_compress(synth.pruned_int8(shape[0], shape[1], 0.5, seed=sum(shape)))
+
+
+def test_compress_device_counting_pass_and_capacity():
+    w = synth.pruned_fp16(100, 4099, 0.5, seed=3)
+    nnz_true = int(np.count_nonzero(w))
+    dense = torch.from_numpy(w.view(np.int16)).cuda()
+    # capacity 0: nothing is written to values, the count still comes back
+    guard = torch.full((64,), POISON, dtype=torch.int16, device="cuda")
+    with pytest.raises(endor.EndorError):
+        endor.compress_device(dense, values=guard[:0])
+    assert torch.all(guard == POISON)
+    # capacity one short of nnz: the last value is not written, nothing past the buffer is touched
+    buf = torch.full((nnz_true + 63,), POISON, dtype=torch.int16, device="cuda")
+    with pytest.raises(endor.EndorError):
+        endor.compress_device(dense, values=buf[: nnz_true - 1])
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint16)
+    assert np.all(host[nnz_true - 1:] == POISON)
+    assert np.array_equal(host[: nnz_true - 1], orc.compress(w)[1][: nnz_true - 1])
+
+
+def test_compress_device_unaligned_dense_and_values():
+    rows, cols = 31, 4101
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=4)
+    big = torch.zeros(1 + rows * cols, dtype=torch.int16, device="cuda")
+    big[1:] = torch.from_numpy(w.view(np.int16)).cuda().reshape(-1)
+    dense = big[1:].view(rows, cols)                     # 2-byte aligned only
+    vbuf = torch.full((3 + rows * cols,), POISON, dtype=torch.int16, device="cuda")
+    m, ws, _ = endor.compress_device(dense, values=vbuf[3:])
+    torch.cuda.synchronize()
+    b, v, _ = orc.compress(w)
+    assert np.array_equal(m.values.cpu().numpy().view(np.uint16), v)
+    assert np.array_equal(m.bitmap.cpu().numpy()[: b.size], b)
+    assert torch.all(vbuf[:3] == POISON) and torch.all(vbuf[3 + v.size:] == POISON)
+
+
+def test_compress_device_full_size_down_proj():
+    _say("device compress full size")
+    w = synth.pruned_fp16(8192, 28672, 0.5, seed=synth.seed_for(4, 0))
+    _check_device_compress(w)
