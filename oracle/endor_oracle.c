@@ -187,3 +187,69 @@ void oracle_decompress_selected_rows(int elem_bytes, int64_t cols,
         }
     }
 }
+
+/*
+ * IEEE 754 binary16 -> double, exact (every binary16 value is a double).
+ * sign 1 bit, exponent 5 bits (bias 15), fraction 10 bits; exponent 0 is zero or
+ * subnormal (fraction * 2^-24), exponent 31 is Inf (fraction 0) or NaN.
+ */
+double oracle_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int exp = (h >> 10) & 0x1F;
+    int frac = h & 0x3FF;
+    double mag;
+    if (exp == 0) {
+        mag = (double)frac / 16777216.0; /* frac * 2^-24 */
+    } else if (exp == 31) {
+        if (frac == 0) {
+            mag = 1.0 / 0.0;
+        } else {
+            double nan = 0.0 / 0.0;
+            return nan;
+        }
+    } else {
+        /* (1 + frac/1024) * 2^(exp-15) */
+        mag = 1.0 + (double)frac / 1024.0;
+        int e = exp - 15;
+        while (e > 0) { mag *= 2.0; --e; }
+        while (e < 0) { mag *= 0.5; ++e; }
+    }
+    return sign ? -mag : mag;
+}
+
+void oracle_half_to_double_array(const uint16_t *h, int64_t n, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = oracle_half_to_double(h[i]);
+}
+
+/*
+ * The dense matrix-vector product the decompressed weight is used for (the paper's
+ * linear operations at batch 1, Section 3.1; computing on the compressed form
+ * directly is the direction Section 7 "Efficient Compute Unit" points to):
+ *     y[i] = sum_j W[i][j] * x[j]
+ * with W the output of Algorithm 2 (fp16 elements), x fp16, everything converted
+ * exactly to double and accumulated in double, j ascending.  Positions whose bit
+ * is 0 hold +0.0 and take part in the sum like any other element, exactly as in a
+ * product with the dense matrix (so a non-finite x[j] propagates the same way).
+ */
+void oracle_gemv_f16(int64_t rows, int64_t cols, const uint8_t *bitmap, const uint16_t *values,
+                     const uint16_t *x, double *y)
+{
+    int64_t k = 0;
+    for (int64_t i = 0; i < rows; ++i) {
+        double acc = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            int64_t e = i * cols + j;
+            double w;
+            if ((bitmap[e >> 3] >> (e & 7)) & 1) {
+                w = oracle_half_to_double(values[k]);
+                k += 1;
+            } else {
+                w = 0.0;
+            }
+            acc += w * oracle_half_to_double(x[j]);
+        }
+        y[i] = acc;
+    }
+}

@@ -58,6 +58,10 @@ def _load():
             lib.oracle_tile_offsets.argtypes = [_i64, _i64, _p, _p]
             lib.oracle_decompress_selected_rows.restype = None
             lib.oracle_decompress_selected_rows.argtypes = [ctypes.c_int, _i64, _p, _i64, _p, _p, _p, _p]
+            lib.oracle_half_to_double_array.restype = None
+            lib.oracle_half_to_double_array.argtypes = [_p, _i64, _p]
+            lib.oracle_gemv_f16.restype = None
+            lib.oracle_gemv_f16.argtypes = [_i64, _i64, _p, _p, _p, _p]
             _lib = lib
     return _lib
 
@@ -171,3 +175,26 @@ def decompress_threaded(rows: int, cols: int, bitmap: np.ndarray, values: np.nda
     for t in range(threads):
         assert ends[t] == int(row_offs[bounds[t + 1]])
     return out
+
+
+def half_to_double(h: np.ndarray) -> np.ndarray:
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float64)
+    lib.oracle_half_to_double_array(_ptr(h), h.size, _ptr(out))
+    return out
+
+
+def gemv_f16(rows: int, cols: int, bitmap: np.ndarray, values: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """y = W x in double, W the Algorithm-2 output of (bitmap, values), x fp16 patterns."""
+    lib = _load()
+    bitmap = np.ascontiguousarray(bitmap, dtype=np.uint8)
+    values = np.ascontiguousarray(values, dtype=np.uint16)
+    x = np.ascontiguousarray(x).view(np.uint16)
+    if x.size != cols or bitmap.size < bitmap_bytes(rows, cols):
+        raise ValueError("bad sizes")
+    if values.size < int(row_offsets(rows, cols, bitmap)[-1]):
+        raise ValueError("values shorter than the number of 1 bits")
+    y = np.empty(rows, dtype=np.float64)
+    lib.oracle_gemv_f16(rows, cols, _ptr(bitmap), _ptr(values), _ptr(x), _ptr(y))
+    return y

@@ -336,3 +336,46 @@ def test_synth_recipe():
     sk = synth.pruned_fp16(2048, 512, 0.5, 11, row_skew=True)
     per_row = (sk != 0).mean(axis=1)
     assert abs(per_row.mean() - 0.5) < 0.02 and 0.18 < per_row.std() < 0.27   # Beta(2,2): sd 0.2236
+
+
+# --------------------------------------------------------------------------
+# the consumer: y = W x on the decompressed matrix
+# --------------------------------------------------------------------------
+def test_half_to_double_is_exact_for_every_pattern():
+    h = np.arange(1 << 16, dtype=np.uint16)
+    got = orc.half_to_double(h)
+    ref = h.view(np.float16).astype(np.float64)          # numpy's own conversion
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok], ref[ok])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(ref[ok]))   # -0.0 keeps its sign
+
+
+def test_gemv_hand_built():
+    # W = [[1.5, 0, -2], [0, 0, 0.5]], x = [2, 100, 0.25]  ->  y = [1.5*2 - 2*0.25, 0.5*0.25] = [2.5, 0.125]
+    W = np.array([[1.5, 0, -2.0], [0, 0, 0.5]], np.float16)
+    b, v, _ = orc.compress(W)
+    y = orc.gemv_f16(2, 3, b, v, np.array([2, 100, 0.25], np.float16))
+    assert y.tolist() == [2.5, 0.125]
+    # transposing the operand or dropping a term gives something else
+    assert y.tolist() != [1.5 * 2, 0.125] and y.tolist() != [3.0 + 50.0, 0.125]
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 5), (7, 13), (33, 65), (5, 4097), (40, 1000)], ids=str)
+def test_gemv_equals_numpy_matmul_in_double(shape):
+    rows, cols = shape
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=rows * 5 + cols)
+    x = (np.random.default_rng(cols).standard_normal(cols)).astype(np.float16)
+    b, v, _ = orc.compress(w)
+    y = orc.gemv_f16(rows, cols, b, v, x)
+    dense = orc.decompress(rows, cols, b, v).view(np.float16).astype(np.float64)
+    ref = np.array([np.sum(dense[i] * x.astype(np.float64)) for i in range(rows)])   # same order of addition
+    assert np.array_equal(y, ref)
+    assert np.allclose(y, dense @ x.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_gemv_nonfinite_x_propagates_like_the_dense_product():
+    W = np.array([[1.0, 0.0], [0.0, 0.0]], np.float16)
+    b, v, _ = orc.compress(W)
+    y = orc.gemv_f16(2, 2, b, v, np.array([1.0, np.inf], np.float16))
+    assert np.isnan(y[0]) and np.isnan(y[1])             # 0 * inf = nan, as with the dense matrix
