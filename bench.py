@@ -34,6 +34,79 @@ WORKLOADS = {
 }
 
 
+def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
+    """Timings of the entry points beyond plain decompression, each with its own
+    algorithmic byte count (what the operation must move) against the 8 TB/s HBM peak."""
+    big = max(range(len(host)), key=lambda i: host[i].rows * host[i].cols)
+    c = host[big]
+    rows, cols, n, nnz = c.rows, c.cols, c.rows * c.cols, c.nnz
+    m = endor.to_device(c)
+    ro = torch.from_numpy(c.row_offsets).cuda()
+    stream = torch.cuda.current_stream()
+    out = []
+
+    def timed(name, fn, alg_bytes, reps=20, note=""):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        gbs = alg_bytes / ms / 1e6
+        out.append({"name": name, "matrix": [shapes[big][0], rows, cols], "ms": round(ms, 4),
+                    "algorithmic_bytes": int(alg_bytes), "GB/s": round(gbs, 1),
+                    "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "note": note})
+
+    # 8-bit variant, whole path (same bitmap density, one byte per value)
+    w8 = synth.pruned_int8(rows, cols, args.keep, seed=synth.seed_for(cfg, big, 8))
+    c8 = endor.compress(w8, want_row_offsets=False)
+    m8 = endor.to_device(c8)
+    o8 = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    ws8 = torch.empty(max(256, endor.workspace_bytes(rows, cols)), dtype=torch.uint8, device="cuda")
+    timed("decompress_u8", lambda: endor.decompress(m8, out=o8, workspace=ws8), n + n // 8 + c8.nnz,
+          note="endor_decompress_u8: offsets + expand, 1 + 1/8 + p bytes per element")
+    del w8, c8, m8, o8
+
+    # row subset: a tenth of the rows, sorted
+    sel_np = np.sort(np.random.default_rng(5).choice(rows, size=max(1, rows // 10), replace=False)).astype(np.int64)
+    sel = torch.from_numpy(sel_np).cuda()
+    osel = torch.empty((sel_np.size, cols), dtype=torch.int16, device="cuda")
+    nnz_sel = int((c.row_offsets[sel_np + 1] - c.row_offsets[sel_np]).sum())
+    timed("decompress_rows_10pct", lambda: endor.decompress_rows(m, ro, sel, out=osel),
+          2 * sel_np.size * cols + sel_np.size * cols // 8 + 2 * nnz_sel,
+          note="endor_decompress_rows on a sorted random tenth of the rows; bytes of the selected rows only")
+
+    # device-side compressor: dense -> bitmap + values (+ table); two passes over the dense matrix by design
+    dense = endor.decompress(m)
+    vals = torch.empty(n, dtype=torch.int16, device="cuda")
+    bm = torch.empty(endor.bitmap_bytes(rows, cols), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(256, endor.workspace_bytes(rows, cols)), dtype=torch.uint8, device="cuda")
+    nnz_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    L = endor.lib()
+
+    def comp():
+        st = L.endor_compress_device(rows, cols, dense.data_ptr(), bm.data_ptr(), vals.data_ptr(), n, ws.data_ptr(),
+                                     ws.numel(), None, nnz_dev.data_ptr(), stream.cuda_stream)
+        assert st == 0
+    timed("compress_device", comp, 2 * n + n // 8 + 2 * nnz,
+          note="endor_compress_device; algorithmic = one read of dense + bitmap + values written "
+               "(the implementation reads the dense matrix twice)")
+    assert int(nnz_dev.item()) == nnz
+    del dense, vals, bm
+
+    # fused consumer
+    x = torch.randn(cols, device="cuda").to(torch.float16)
+    y = torch.empty(rows, dtype=torch.float32, device="cuda")
+    timed("gemv_f16", lambda: endor.gemv_f16(m, ro, x, y=y), n // 8 + 2 * nnz + 8 * (rows + 1) + 2 * cols + 4 * rows,
+          note="endor_gemv_f16: bitmap + values + row offsets + x read, y written; a dense fp16 GEMV "
+               "would read %d bytes" % (2 * n))
+    return out
+
+
 def overlap_leg(endor, torch, host, outs, args):
     """Pinned host -> device copy of the compressed blobs, alone and overlapped with
     decompression (two streams, double-buffered staging).  PCIe-bound by design: these
@@ -122,6 +195,9 @@ def main() -> int:
                     help="also time the pinned host-to-device copy, alone and pipelined with decompression "
                          "on a second stream (adds an \"overlap\" object)")
     ap.add_argument("--overlap-blocks", type=int, default=4, help="row blocks per matrix in the pipeline")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the widened entry points on the workload's largest matrix: 8-bit "
+                         "variant, row subset, device-side compressor, fused y = W x (adds an \"extras\" list)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (a reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -274,6 +350,8 @@ def main() -> int:
 
     if args.overlap:
         result["overlap"] = overlap_leg(endor, torch, host, outs, args)
+    if args.extras:
+        result["extras"] = extras_leg(endor, synth, torch, np, host, shapes, cfg, args)
 
     if not args.no_cpu_baseline:
         from oracle import endor_oracle as orc

@@ -239,6 +239,20 @@ endor_status endor_compress_device_u8(int64_t rows, int64_t cols, const uint8_t 
                                       int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream);
 
 /*
+ * DEVICE.  Fused consumer: y = W x computed straight from the compressed form, without
+ * writing the dense matrix (the batch-1 linear operation the paper's workload runs on the
+ * decompressed weight, Section 3.1; computing on the sparse form is the direction of
+ * Section 7, "Efficient Compute Unit").  W: fp16 values; x: cols fp16 values (device);
+ * y: rows fp32 results (device), y[i] = sum_j W[i][j]*x[j] with fp16 products exact and
+ * accumulation in fp32.  Elements whose bit is 0 enter as +0.0, as from the dense matrix.
+ * d_row_offsets as for endor_decompress_rows.  16-byte aligned d_x selects the fast path.
+ */
+endor_status endor_gemv_f16(int64_t rows, int64_t cols,
+                            const uint8_t *d_bitmap, const uint16_t *d_values, int64_t nnz,
+                            const int64_t *d_row_offsets,
+                            const uint16_t *d_x, float *d_y, void *stream);
+
+/*
  * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
  * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
  * is copied from host memory to GPU memory and decompressed there; Section 6 notes

@@ -31,7 +31,10 @@
  *       case; the 1-byte case is the INT8 variant of Section 4.2).  No floating
  *       point instruction ever touches a value.
  *
- * Everything here is integer / byte work, so results are exact.
+ * Algorithms 1 and 2 and the tables derived from them are integer / byte work, so
+ * their results are exact.  The one floating-point routine, oracle_gemv_f16 at the
+ * end of the file (the matrix-vector product on the decompressed matrix), converts
+ * fp16 to double exactly and accumulates in double.
  */
 #include <stdint.h>
 #include <stddef.h>

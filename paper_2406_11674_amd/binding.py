@@ -18,7 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
-    "decompress_rows", "compress_device", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
+    "decompress_rows", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_i64, _i64, _p, _p, _p, _i64, _p, _sz, _p, _p, _p]
+        L.endor_gemv_f16.restype = ctypes.c_int
+        L.endor_gemv_f16.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _p, _p]
         L.endor_stage_bytes.restype = _sz
         L.endor_stage_bytes.argtypes = [_i64, _i64, _i64]
         L.endor_h2d_decompress_pipeline.restype = ctypes.c_int
@@ -326,6 +328,18 @@ def compress_device(dense, values=None, row_offsets: bool = False, stream=None):
     if n > values.numel():
         raise EndorError(2, f"endor_compress_device: {n} non-zeros, capacity {values.numel()}")
     return DeviceMatrix(rows, cols, bitmap, values[:n], n), ws, ro
+
+
+def gemv_f16(m: DeviceMatrix, row_offsets, x, y=None, stream=None):
+    """endor_gemv_f16: y (fp32, rows) = W x with W in compressed form, x fp16 (cols)."""
+    torch = _torch()
+    if m.elem_bytes != 2 or x.element_size() != 2 or x.numel() != m.cols:
+        raise ValueError("gemv_f16 needs 16-bit values and an fp16 x of length cols")
+    if y is None:
+        y = torch.empty(m.rows, dtype=torch.float32, device=m.bitmap.device)
+    _check(lib().endor_gemv_f16(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets),
+                                _dptr(x), _dptr(y), _stream_handle(stream)), "endor_gemv_f16")
+    return y
 
 
 # ------------------------------------------------------------------ host -> device pipeline

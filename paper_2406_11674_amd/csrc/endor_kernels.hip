@@ -277,16 +277,46 @@ __device__ __forceinline__ uint32_t byte_mask(uint32_t b) {
            ((b & 8u) ? 0xff000000u : 0u);
 }
 
+// Sink that writes the expanded tile to memory: a 16-byte non-temporal store per lane
+// and step when the tile is complete and the output 16-byte aligned, else element by
+// element with a bounds check.
+template <int E, bool kAlignedOut>
+struct StoreSink {
+    uint8_t *out;     // byte address of the tile's first output element
+    uint32_t nvalid;  // elements of the tile that exist (<= 4096)
+    __device__ __forceinline__ void operator()(int, uint32_t le, u32x4 d) const {
+        if (kAlignedOut && nvalid == kTileElems) {
+#if ENDOR_NT_STORE
+            __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + size_t(le) * E));
+#else
+            *reinterpret_cast<u32x4 *>(out + size_t(le) * E) = d;
+#endif
+        } else {
+            const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int j = 0; j < Shape<E>::kLaneElems; ++j) {
+                if (le + j < nvalid) {
+                    const uint32_t v = dd[(E * j) >> 2] >> (8 * ((E * j) & 3));
+                    if (E == 2)
+                        reinterpret_cast<uint16_t *>(out)[le + j] = static_cast<uint16_t>(v);
+                    else
+                        out[le + j] = static_cast<uint8_t>(v);
+                }
+            }
+        }
+    }
+};
+
 // Expand one tile with one wave.
 //   word     this lane's 64 bitmap bits of the tile (bits past the end already cleared)
 //   vaddr    byte address of the tile's first value; cnt = number of 1 bits in the tile
 //   [vbeg, vend)  the byte range of the whole `values` array (nothing outside is read)
-//   out      byte address of the tile's first output element; nvalid <= 4096 elements are written
+//   sink     receives, per step k, the 16 expanded bytes of this lane: sink(k, le, d) with le
+//            the index inside the tile of the lane's first element
 // The caller has not touched S since the wave's previous call returned.
-template <int E, bool kAlignedOut>
+template <int E, class Sink>
 __device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, uint64_t word, uintptr_t vaddr,
-                                            uint32_t cnt, uintptr_t vbeg, uintptr_t vend, uint8_t *out,
-                                            uint32_t nvalid) {
+                                            uint32_t cnt, uintptr_t vbeg, uintptr_t vend, Sink &sink) {
     using Sh = Shape<E>;
     // --- issue the loads of the tile's value slice (16-byte units from the 16-byte
     //     boundary at or below its first value)
@@ -318,7 +348,6 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, ui
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // --- expand: per step every lane turns kLaneElems bitmap bits into 16 bytes of output
-    const bool full_tile = nvalid == kTileElems;
 #pragma unroll
     for (int k = 0; k < Sh::kSteps; ++k) {
         const uint32_t wi = k * Sh::kLaneElems + lane / Sh::kLanesPerWord;
@@ -326,6 +355,10 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, ui
         const uint32_t sh = (lane % Sh::kLanesPerWord) * Sh::kLaneElems;
         const uint32_t bits = static_cast<uint32_t>(w >> sh) & ((1u << Sh::kLaneElems) - 1);
         const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
+        // every element is read from the staging area at its rank; the ones whose bit is 0
+        // pick up a neighbour's value and are masked to the all-zero pattern.  (Measured
+        // alternatives that lost: one 32-bit read per output dword plus a byte permutation,
+        // with misaligned reads 1.8x slower, with aligned pairs and a funnel shift 1.0-1.4x.)
         u32x4 d;
         if (E == 2) {
             const uint16_t *sp = reinterpret_cast<const uint16_t *>(S.stage) + s;
@@ -346,26 +379,7 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, ui
             d.z = (h[8] | (h[9] << 8) | (h[10] << 16) | (h[11] << 24)) & byte_mask(bits >> 8);
             d.w = (h[12] | (h[13] << 8) | (h[14] << 16) | (h[15] << 24)) & byte_mask(bits >> 12);
         }
-        const uint32_t le = (k * 64 + lane) * Sh::kLaneElems;  // element index inside the tile
-        if (kAlignedOut && full_tile) {
-#if ENDOR_NT_STORE
-            __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + size_t(le) * E));
-#else
-            *reinterpret_cast<u32x4 *>(out + size_t(le) * E) = d;
-#endif
-        } else {
-            const uint32_t dd[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-            for (int j = 0; j < Sh::kLaneElems; ++j) {
-                if (le + j < nvalid) {
-                    const uint32_t v = dd[(E * j) >> 2] >> (8 * ((E * j) & 3));
-                    if (E == 2)
-                        reinterpret_cast<uint16_t *>(out)[le + j] = static_cast<uint16_t>(v);
-                    else
-                        out[le + j] = static_cast<uint8_t>(v);
-                }
-            }
-        }
+        sink(k, (k * 64 + lane) * Sh::kLaneElems, d);
     }
     // the next tile's LDS writes must stay behind this tile's LDS reads
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -403,10 +417,31 @@ __global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams 
         const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
         const int64_t e0 = tile * kTileElems;
         const int64_t left = n - e0;
-        expand_tile<E, kAlignedOut>(s_scratch[wave], lane, word, vbeg + E * (base + o0), cnt, vbeg, vend,
-                                    reinterpret_cast<uint8_t *>(M.dense) + e0 * E,
-                                    left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems));
+        StoreSink<E, kAlignedOut> sink{reinterpret_cast<uint8_t *>(M.dense) + e0 * E,
+                                       left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems)};
+        expand_tile<E>(s_scratch[wave], lane, word, vbeg + E * (base + o0), cnt, vbeg, vend, sink);
     }
+}
+
+// This lane's 64 bits of a segment of `nbits` (<= 4096) bits that starts at an arbitrary
+// bit position e of the bitmap: bits e + 64*lane .. +63, funnelled out of two neighbouring
+// words, with everything past the segment (or past the bitmap) cleared.
+__device__ __forceinline__ uint64_t segment_word(const uint64_t *bitmap, int64_t nwords, int64_t e,
+                                                 uint32_t nbits, uint32_t lane) {
+    uint64_t word = 0;
+    if (lane * 64 < nbits) {
+        const int64_t w0 = (e >> 6) + lane;
+        const uint32_t bs = static_cast<uint32_t>(e & 63);
+        const uint64_t lo = w0 < nwords ? bitmap[w0] : 0;
+        word = lo >> bs;
+        if (bs != 0) {
+            const uint64_t hi = w0 + 1 < nwords ? bitmap[w0 + 1] : 0;
+            word |= hi << (64 - bs);
+        }
+        const uint32_t rem = nbits - lane * 64;  // bits of this lane that belong to the segment
+        if (rem < 64) word &= (uint64_t(1) << rem) - 1;
+    }
+    return word;
 }
 
 // ---------------------------------------------------------------- kernel 2b: selected rows
@@ -455,28 +490,108 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
         before = wave_sum(before);
     }
 
-    // this lane's 64 bits of the segment, taken from bit position e + 64*lane
-    const int64_t w0 = (e >> 6) + lane;
-    const uint32_t bs = static_cast<uint32_t>(e & 63);
-    uint64_t word = 0;
-    if (lane * 64 < nbits) {
-        const uint64_t lo = w0 < nwords ? R.bitmap[w0] : 0;
-        word = lo >> bs;
-        if (bs != 0) {
-            const uint64_t hi = w0 + 1 < nwords ? R.bitmap[w0 + 1] : 0;
-            word |= hi << (64 - bs);
-        }
-        const uint32_t rem = nbits - lane * 64;  // bits of this lane that belong to the segment
-        if (rem < 64) word &= (uint64_t(1) << rem) - 1;
-    }
+    const uint64_t word = segment_word(R.bitmap, nwords, e, nbits, lane);
     const uint32_t cnt = wave_sum(__popcll(word));
 
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(R.values);
     const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(R.nnz);
     const uint64_t first = static_cast<uint64_t>(R.row_offsets[i]) + before;
-    expand_tile<E, kAlignedOut>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend,
-                                reinterpret_cast<uint8_t *>(R.out) + (r * R.cols + int64_t(g) * kTileElems) * E,
-                                nbits);
+    StoreSink<E, kAlignedOut> sink{
+        reinterpret_cast<uint8_t *>(R.out) + (r * R.cols + int64_t(g) * kTileElems) * E, nbits};
+    expand_tile<E>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend, sink);
+}
+
+// ---------------------------------------------------------------- fused consumer: y = W x
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float wave_sum_f32(float x) {
+    // same lane order as wave_inclusive_scan, so the result does not depend on timing
+#define ENDOR_DPP_ADD_F32(ctrl, rowmask)                                                                     \
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, rowmask, \
+                                                               0xf, true))
+    ENDOR_DPP_ADD_F32(0x111, 0xf);
+    ENDOR_DPP_ADD_F32(0x112, 0xf);
+    ENDOR_DPP_ADD_F32(0x114, 0xf);
+    ENDOR_DPP_ADD_F32(0x118, 0xf);
+    ENDOR_DPP_ADD_F32(0x142, 0xa);
+    ENDOR_DPP_ADD_F32(0x143, 0xc);
+#undef ENDOR_DPP_ADD_F32
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// Sink that multiplies the expanded fp16 elements with the matching 8 entries of x and
+// accumulates in fp32.  Each product of two fp16 numbers is exact in fp32 and each step is
+// one fused multiply-add with fp16 operands widened in the instruction (v_fma_mix_f32), so
+// fp16 subnormals count in full (the packed dot-product instructions flush them).
+struct GemvSink {
+    u32x4 xs[Shape<2>::kSteps];  // x[le .. le+7] for each step of the current segment
+    float acc;
+    __device__ __forceinline__ void pair(uint32_t w2, uint32_t x2) {
+#pragma clang fp contract(off)  // keep the two multiply-adds apart: fused into a dot product they would flush
+        const f16x2 w = __builtin_bit_cast(f16x2, w2);
+        const f16x2 x = __builtin_bit_cast(f16x2, x2);
+        acc = __builtin_fmaf(static_cast<float>(w.x), static_cast<float>(x.x), acc);
+        acc = __builtin_fmaf(static_cast<float>(w.y), static_cast<float>(x.y), acc);
+    }
+    __device__ __forceinline__ void operator()(int k, uint32_t, u32x4 d) {
+        pair(d.x, xs[k].x);
+        pair(d.y, xs[k].y);
+        pair(d.z, xs[k].z);
+        pair(d.w, xs[k].w);
+    }
+};
+
+struct GemvParams {
+    const uint64_t *bitmap;
+    const uint16_t *values;
+    const int64_t *row_offsets;  // rows + 1
+    const uint16_t *x;           // cols fp16
+    float *y;                    // rows fp32
+    int64_t rows, cols, nnz;
+};
+
+// y[i] = sum_j W[i][j] * x[j] straight from the compressed form: the dense row is never
+// written.  One wave per row walks the row's 4096-column segments, expanding each into
+// registers exactly as the decompressor does and feeding the fp16 pairs to dot products.
+// Elements whose bit is 0 enter as +0.0, as they would from the dense matrix.
+__global__ __launch_bounds__(64) void endor_gemv_f16_kernel(GemvParams G) {
+    __shared__ WaveScratch<2> s_scratch;
+    const uint32_t lane = threadIdx.x;
+    const int64_t i = blockIdx.x;
+    const int64_t nwords = (G.rows * G.cols + 63) >> 6;
+    const int64_t row_bit = i * G.cols;
+    const uintptr_t vbeg = reinterpret_cast<uintptr_t>(G.values);
+    const uintptr_t vend = vbeg + 2 * static_cast<uintptr_t>(G.nnz);
+    const bool x16 = (reinterpret_cast<uintptr_t>(G.x) & 15) == 0;
+    uint64_t next_value = static_cast<uint64_t>(G.row_offsets[i]);
+    GemvSink sink;
+    sink.acc = 0.0f;
+    for (int64_t c0 = 0; c0 < G.cols; c0 += kTileElems) {
+        const int64_t left = G.cols - c0;
+        const uint32_t nbits = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+        const uint64_t word = segment_word(G.bitmap, nwords, row_bit + c0, nbits, lane);
+        const uint32_t cnt = wave_sum(__popcll(word));
+#pragma unroll
+        for (int k = 0; k < Shape<2>::kSteps; ++k) {
+            const uint32_t le = (k * 64 + lane) * 8;
+            if (x16 && le + 8 <= nbits) {
+                sink.xs[k] = *reinterpret_cast<const u32x4 *>(G.x + c0 + le);
+            } else {
+                uint32_t h[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) h[j] = (le + j < nbits) ? uint32_t(G.x[c0 + le + j]) : 0u;
+                sink.xs[k].x = h[0] | (h[1] << 16);
+                sink.xs[k].y = h[2] | (h[3] << 16);
+                sink.xs[k].z = h[4] | (h[5] << 16);
+                sink.xs[k].w = h[6] | (h[7] << 16);
+            }
+        }
+        expand_tile<2>(s_scratch, lane, word, vbeg + 2 * next_value, cnt, vbeg, vend, sink);
+        next_value += cnt;
+    }
+    const float total = wave_sum_f32(sink.acc);
+    if (lane == 0) G.y[i] = total;
 }
 
 // ---------------------------------------------------------------- device-side compression
@@ -1075,4 +1190,36 @@ extern "C" endor_status endor_compress_device_u8(int64_t rows, int64_t cols, con
                                                  int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream) {
     return run_compress_device<1>(rows, cols, d_dense, d_bitmap, d_values, values_capacity, d_workspace,
                                   workspace_bytes, d_row_offsets, d_nnz_out, stream);
+}
+
+// ---------------------------------------------------------------- fused consumer
+
+extern "C" endor_status endor_gemv_f16(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                       const uint16_t *d_values, int64_t nnz, const int64_t *d_row_offsets,
+                                       const uint16_t *d_x, float *d_y, void *stream) {
+    if (rows < 0 || cols < 0 || nnz < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    if (rows == 0) return ENDOR_OK;
+    if (rows > 0x7fffffff) return ENDOR_ERR_UNSUPPORTED;
+    if (!d_y || (reinterpret_cast<uintptr_t>(d_y) & 3)) return ENDOR_ERR_INVALID_ARG;
+    if (!d_row_offsets || (reinterpret_cast<uintptr_t>(d_row_offsets) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (cols > 0) {
+        if (nnz > rows * cols) return ENDOR_ERR_INVALID_ARG;
+        if (!d_bitmap || (reinterpret_cast<uintptr_t>(d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
+        if (!d_x || (reinterpret_cast<uintptr_t>(d_x) & 1)) return ENDOR_ERR_INVALID_ARG;
+        if (nnz > 0 && (!d_values || (reinterpret_cast<uintptr_t>(d_values) & 1))) return ENDOR_ERR_INVALID_ARG;
+    }
+    GemvParams G;
+    G.bitmap = reinterpret_cast<const uint64_t *>(d_bitmap);
+    G.values = d_values;
+    G.row_offsets = d_row_offsets;
+    G.x = d_x;
+    G.y = d_y;
+    G.rows = rows;
+    G.cols = cols;
+    G.nnz = nnz;
+    hipLaunchKernelGGL(endor_gemv_f16_kernel, dim3(static_cast<unsigned>(rows)), dim3(64), 0,
+                       static_cast<hipStream_t>(stream), G);
+    if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    return ENDOR_OK;
 }

@@ -507,3 +507,90 @@ def test_compress_device_full_size_down_proj():
     _say("device compress full size")
     w = synth.pruned_fp16(8192, 28672, 0.5, seed=synth.seed_for(4, 0))
     _check_device_compress(w)
+
+
+# ---------------------------------------------------------------------------
+# fused consumer: y = W x straight from the compressed form (fp32 accumulation)
+# ---------------------------------------------------------------------------
+def _gemv_tolerance(w_bits, x16, cols):
+    """fp16 products are exact in fp32; every fp32 addition on the longest chain (a lane adds
+    cols/64 products one after the other, then 6 adds across lanes and one more) contributes
+    at most 2^-24 of the running magnitude, so |err_i| <= (cols/64 + 8) * 2^-24 * sum_j |W_ij x_j|
+    (plus one ulp of the smallest normal for underflow)."""
+    absw = np.abs(w_bits.view(np.float16).astype(np.float64))
+    absx = np.abs(x16.astype(np.float64))
+    return (cols / 64 + 8) * 2.0 ** -24 * 1.01 * (absw @ absx) + 2.0 ** -126
+
+
+GEMV_SHAPES = [(1, 1), (3, 5), (7, 13), (33, 65), (5, 4095), (5, 4096), (5, 4097), (40, 1000), (64, 8192),
+               (16, 28672), (9, 12345)]
+
+
+@pytest.mark.parametrize("shape", GEMV_SHAPES, ids=str)
+def test_gemv_matches_oracle(shape):
+    rows, cols = shape
+    _say(f"gemv case shape={shape}")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=rows * 5 + cols, row_skew=True)
+    w.reshape(-1)[:: 97] = 0x0001                      # fp16 subnormals among the values
+    x16 = np.random.default_rng(cols).standard_normal(cols).astype(np.float16)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    ro = torch.from_numpy(c.row_offsets).cuda()
+    y = endor.gemv_f16(m, ro, torch.from_numpy(x16).cuda())
+    torch.cuda.synchronize()
+    ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - ref)
+    tol = _gemv_tolerance(w, x16, cols)
+    assert np.all(err <= tol), (err.max(), tol[np.argmax(err)])
+
+
+def test_gemv_unaligned_x_and_device_row_offsets():
+    rows, cols = 50, 9001
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=3)
+    x16 = np.random.default_rng(1).standard_normal(cols).astype(np.float16)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    _, ro = endor.build_offsets(m, row_offsets=True)
+    xbuf = torch.zeros(cols + 1, dtype=torch.float16, device="cuda")
+    xbuf[1:] = torch.from_numpy(x16).cuda()
+    y = endor.gemv_f16(m, ro, xbuf[1:])
+    torch.cuda.synchronize()
+    ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= _gemv_tolerance(w, x16, cols))
+
+
+def test_gemv_nonfinite_x_like_the_dense_product():
+    rows, cols = 4, 100
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=9)
+    w[0, 7] = 0            # a zero element meets x = inf: 0 * inf = nan, as with the dense matrix
+    w[1, 7] = 0x3C00       # 1.0 meets inf: +inf (unless other terms make it nan)
+    x16 = np.random.default_rng(2).standard_normal(cols).astype(np.float16)
+    x16[7] = np.inf
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    y = endor.gemv_f16(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(x16).cuda())
+    torch.cuda.synchronize()
+    ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(np.isinf(got), np.isinf(ref))
+
+
+@pytest.mark.parametrize("shape", [(8192, 28672), (28672, 8192)], ids=["down_proj", "gate_proj"])
+def test_gemv_full_size(shape):
+    rows, cols = shape
+    _say(f"gemv full size {shape}")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=synth.seed_for(3, 6 if rows == 8192 else 4))
+    x16 = np.random.default_rng(11).standard_normal(cols).astype(np.float16)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    y = endor.gemv_f16(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(x16).cuda())
+    torch.cuda.synchronize()
+    # oracle on a sample of rows (the whole product is 235 M double multiply-adds per matrix:
+    # affordable, but the sample keeps the suite short); every sampled row is checked in full
+    sample = np.unique(np.concatenate([[0, rows - 1], np.random.default_rng(3).integers(0, rows, 400)]))
+    dense = orc.decompress_selected_rows(cols, sample.astype(np.int64), c.row_offsets, c.bitmap, c.values)
+    sb, sv, _ = orc.compress(dense)
+    ref = orc.gemv_f16(sample.size, cols, sb, sv, x16)
+    err = np.abs(y.cpu().numpy().astype(np.float64)[sample] - ref)
+    assert np.all(err <= _gemv_tolerance(dense, x16, cols))
