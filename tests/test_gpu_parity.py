@@ -594,3 +594,33 @@ def test_gemv_full_size(shape):
     ref = orc.gemv_f16(sample.size, cols, sb, sv, x16)
     err = np.abs(y.cpu().numpy().astype(np.float64)[sample] - ref)
     assert np.all(err <= _gemv_tolerance(dense, x16, cols))
+
+
+# ---------------------------------------------------------------------------
+# the device entry points only enqueue kernels: they can be captured into a HIP graph
+# ---------------------------------------------------------------------------
+def test_decompress_batch_in_a_hip_graph_replays_correctly():
+    shapes = [(300, 4099), (64, 4096), (1031, 2053)]
+    cs = [endor.compress(synth.pruned_fp16(r, c, 0.5, seed=60 + i)) for i, (r, c) in enumerate(shapes)]
+    mats = [endor.to_device(c) for c in cs]
+    outs = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in cs]
+    ws = torch.empty(max(256, endor.batch_workspace_bytes(mats)), dtype=torch.uint8, device="cuda")
+    expect = [orc.decompress(c.rows, c.cols, c.bitmap, c.values) for c in cs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        endor.decompress_batch(mats, outs=outs, workspace=ws, stream=side)     # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        endor.decompress_batch(mats, outs=outs, workspace=ws, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        for o in outs:                      # eager work and a synchronisation between replays
+            o.fill_(POISON)
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, expect):
+            assert np.array_equal(o.cpu().numpy().view(np.uint16), e), f"replay {rep}"
