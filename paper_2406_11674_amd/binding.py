@@ -24,7 +24,8 @@ __all__ = [
 TILE_ELEMS = 4096
 MAX_BATCH = 16
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libendor.so")
+# ENDOR_LIBRARY points at another build of the same library (kernel tuning experiments)
+_LIB_PATH = os.environ.get("ENDOR_LIBRARY") or os.path.join(_HERE, "libendor.so")
 _lib = None
 
 _i64 = ctypes.c_int64
