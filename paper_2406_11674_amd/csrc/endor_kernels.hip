@@ -34,7 +34,10 @@ namespace {
 
 constexpr int kTileElems = ENDOR_TILE_ELEMS;  // flat positions per tile
 constexpr int kTileWords = kTileElems / 64;   // 64-bit bitmap words per tile (= lanes per wave)
-constexpr int kTilesPerChunk = 256;           // tiles one count workgroup covers
+#ifndef ENDOR_TILES_PER_CHUNK
+#define ENDOR_TILES_PER_CHUNK 256
+#endif
+constexpr int kTilesPerChunk = ENDOR_TILES_PER_CHUNK;  // tiles one count workgroup covers
 constexpr int kChunkStride = kTilesPerChunk + 1;
 constexpr int kBlock = 256;                   // threads per workgroup of the row-offset kernel
 constexpr int kWaves = kBlock / 64;

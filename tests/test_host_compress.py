@@ -102,3 +102,21 @@ def test_compress_u8_matches_oracle(shape, keep):
     assert np.array_equal(c.row_offsets, r)
     # compressed size of the 8-bit variant: N/8 + nnz bytes
     assert b.nbytes + c.values.nbytes == (rows * cols + 7) // 8 + int(np.count_nonzero(w))
+
+
+@pytest.mark.parametrize("rows,cols,nblocks", [(2048, 4096, 8), (1031, 2053, 5), (96, 24, 3), (333, 64, 50), (5, 7, 3)])
+def test_row_blocks_are_self_contained_blobs(rows, cols, nblocks):
+    """A block of whole rows, cut where row*cols is a bitmap word boundary, is a valid
+    compressed matrix of its own: the oracle's Algorithm 2 on the block gives the block's rows."""
+    torch = pytest.importorskip("torch")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=50, row_skew=True)
+    c = endor.compress(w)
+    bm = torch.from_numpy(c.bitmap.copy())
+    vals = torch.from_numpy(c.values.view(np.int16).copy())
+    blobs = endor.row_blocks(c, (bm, vals), nblocks)
+    assert sum(b.rows for b in blobs) == rows and sum(b.nnz for b in blobs) == c.nnz
+    for b in blobs:
+        assert (b.row_begin * cols) % 64 == 0
+        sub = orc.decompress(b.rows, cols, b.bitmap.numpy()[: endor.bitmap_bytes(b.rows, cols)],
+                             b.values.numpy().view(np.uint16))
+        assert np.array_equal(sub, w[b.row_begin:b.row_begin + b.rows])
