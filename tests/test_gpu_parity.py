@@ -624,3 +624,71 @@ def test_decompress_batch_in_a_hip_graph_replays_correctly():
         torch.cuda.synchronize()
         for o, e in zip(outs, expect):
             assert np.array_equal(o.cpu().numpy().view(np.uint16), e), f"replay {rep}"
+
+
+# ---------------------------------------------------------------------------
+# more than 2^32 elements / values: 64-bit indexing everywhere
+# ---------------------------------------------------------------------------
+def test_more_than_2_pow_32_values_all_bits_set():
+    """Every bit 1 => the output is the value stream itself (the special case the oracle is
+    pinned on), checked on the device.  N = nnz = 2^32 + 2^20."""
+    rows, cols = 4097, 1 << 20
+    n = rows * cols
+    _say(f"2^32 test: all ones, n={n}")
+    period = 65521                                     # prime, so no power-of-two shift goes unnoticed
+    base = torch.arange(period, device="cuda").to(torch.int16)
+    values = base.repeat((n + period - 1) // period)[:n].contiguous()
+    bitmap = torch.full((endor.bitmap_bytes(rows, cols),), 0xFF, dtype=torch.uint8, device="cuda")
+    m = endor.DeviceMatrix(rows, cols, bitmap, values, n)
+    out = torch.full((rows, cols), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(-1), values)
+    _, ro = endor.build_offsets(m, row_offsets=True)
+    torch.cuda.synchronize()
+    assert torch.equal(ro, torch.arange(rows + 1, device="cuda", dtype=torch.int64) * cols)
+
+
+def test_more_than_2_pow_32_elements_sparse_random():
+    """N = 2^32 + 2^20, one element in eight kept at random.  Whole output against a
+    mask-scatter built with torch on the device, slab by slab; sampled rows (the first, the
+    last, those around flat index 2^32) against the oracle's Algorithm 2."""
+    rows, cols = 4097, 1 << 20
+    n = rows * cols
+    _say(f"2^32 test: sparse random, n={n}")
+    g = np.random.default_rng(2032)
+    nbytes = n // 8
+    bm = g.integers(0, 256, nbytes, dtype=np.uint8)
+    bm &= g.integers(0, 256, nbytes, dtype=np.uint8)
+    bm &= g.integers(0, 256, nbytes, dtype=np.uint8)
+    per_row = np.bitwise_count(bm.view(np.uint64).reshape(rows, -1)).sum(axis=1, dtype=np.int64)
+    row_offs = np.concatenate([[0], np.cumsum(per_row)]).astype(np.int64)
+    nnz = int(row_offs[-1])
+    values = g.integers(0, 1 << 16, nnz, dtype=np.uint16)
+    c = endor.Compressed(rows, cols, bm, values, row_offs)
+    m = endor.to_device(c)
+    out = torch.full((rows, cols), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress(m, out=out)
+    _, ro = endor.build_offsets(m, row_offsets=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(ro.cpu().numpy(), row_offs)
+    # the whole output, slab by slab, against torch's masked_scatter_
+    shifts = torch.arange(8, device="cuda", dtype=torch.uint8)
+    slab = 256
+    for r0 in range(0, rows, slab):
+        r1 = min(rows, r0 + slab)
+        bytes_ = m.bitmap[r0 * cols // 8: r1 * cols // 8]
+        mask = ((bytes_[:, None] >> shifts) & 1).bool().view(r1 - r0, cols)
+        expect = torch.zeros((r1 - r0, cols), dtype=torch.int16, device="cuda")
+        expect.masked_scatter_(mask, m.values[int(row_offs[r0]):int(row_offs[r1])])
+        assert torch.equal(out[r0:r1], expect), f"rows {r0}..{r1}"
+        del mask, expect
+    # sampled rows against the oracle
+    sel = np.array([0, 1, 2047, 4094, 4095, 4096], np.int64)      # row 4096 starts at flat index 2^32
+    expect = orc.decompress_selected_rows(cols, sel, row_offs, bm, values)
+    got = out[torch.from_numpy(sel).cuda()].cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, expect)
+    # and the row-subset entry point at the same offsets
+    rsel = endor.decompress_rows(m, ro, torch.from_numpy(sel).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(rsel.cpu().numpy().view(np.uint16), expect)
