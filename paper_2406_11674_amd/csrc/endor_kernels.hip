@@ -13,17 +13,25 @@
 //      relative to the chunk start plus the chunk's total.
 //   2. endor_expand_kernel: one single-wave workgroup per tile, waves fully
 //      independent (no workgroup barrier; measured faster on MI355X than wider
-//      workgroups or several tiles per wave).  The wave adds up the totals of the chunks before its
-//      own (a few loads per lane) to get the chunk's absolute start, stages the
-//      tile's contiguous slice of `values` into LDS with 16-byte loads, scans the
-//      64 word popcounts across lanes (DPP), and then, in 8 steps of 512 elements,
-//      every lane turns one bitmap byte into 8 output elements (8 LDS reads at
-//      rank-within-byte offsets, masked by the bits) and issues one 16-byte store,
-//      so a wave writes 1 KiB of contiguous dense output per store instruction.
+//      workgroups or several tiles per wave).  The wave adds up the totals of the
+//      chunks before its own (a few loads per lane) to get the chunk's absolute
+//      start, stages the tile's contiguous slice of `values` into LDS with 16-byte
+//      loads, scans the 64 word popcounts across lanes (DPP), and then, in 8 steps
+//      of 512 elements, every lane turns one bitmap byte into 8 output elements
+//      (8 LDS reads at rank-within-byte offsets, masked by the bits) and issues one
+//      16-byte store, so a wave writes 1 KiB of contiguous dense output per store
+//      instruction.
 //
-// The path is bound by HBM traffic (2 bytes written, 1/8 + 2p bytes read per
-// element), so there is no matrix-core work here; all arithmetic is integer and
-// the values are only ever moved, never interpreted.
+// The same tile expander, fed differently or draining into a different sink, gives
+// the row-subset kernel (Section 4.2's selective load), the matrix-vector product on
+// the compressed form, and - run backwards, as a scatter - the pack step of the
+// device-side compressor (Algorithm 1).  The element width (2 bytes, or 1 for the
+// 8-bit variant of Section 4.2) is a template parameter throughout.
+//
+// The path is bound by memory traffic (2 bytes written, 1/8 + 2p bytes read per
+// element), so there is no matrix-core work here; all arithmetic on the format is
+// integer and the values are only ever moved, never interpreted (the product kernel
+// apart).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -573,7 +581,7 @@ struct GemvParams {
 
 // y[i] = sum_j W[i][j] * x[j] straight from the compressed form: the dense row is never
 // written.  One wave per row walks the row's 4096-column segments, expanding each into
-// registers exactly as the decompressor does and feeding the fp16 pairs to dot products.
+// registers exactly as the decompressor does and feeding the fp16 pairs to multiply-adds.
 // Elements whose bit is 0 enter as +0.0, as they would from the dense matrix.
 __global__ __launch_bounds__(64) void endor_gemv_f16_kernel(GemvParams G) {
     __shared__ WaveScratch<2> s_scratch;
