@@ -71,3 +71,20 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libendor.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.lib()
+
+
+def test_header_is_valid_c99_and_cxx17(tmp_path):
+    """include/endor.h is a C header: it must compile on its own as C99 and as C++17."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None or shutil.which("g++") is None:
+        pytest.skip("needs gcc and g++")
+    src_c = tmp_path / "use.c"
+    src_c.write_text('#include "endor.h"\nint main(void) { return (int)endor_bitmap_bytes(1, 1) == 8 ? 0 : 1; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c",
+                           str(src_c), "-o", str(tmp_path / "use_c.o")])
+    src_cpp = tmp_path / "use.cpp"
+    src_cpp.write_text(src_c.read_text())
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c",
+                           str(src_cpp), "-o", str(tmp_path / "use_cpp.o")])
