@@ -126,6 +126,16 @@ endor_status endor_build_offsets(int64_t rows, int64_t cols, const uint8_t *d_bi
                                  int64_t *d_row_offsets, void *stream);
 
 /*
+ * HOST.  The same table built on the host, e.g. once at compression time (the paper
+ * compresses before inference, Section 4.1 "Compression"), into a host buffer of
+ * endor_workspace_bytes() bytes that is then copied to the device next to the blob and
+ * used with the *_with_offsets entry points; no device pass over the bitmap is needed
+ * then.  Every table entry equals what endor_build_offsets writes.
+ */
+endor_status endor_build_offsets_host(int64_t rows, int64_t cols, const uint8_t *bitmap,
+                                      void *workspace, size_t workspace_bytes);
+
+/*
  * DEVICE.  Algorithm 2 (Section 4.1, "Decompression") in parallel form: every one
  * of the rows*cols output elements is written exactly once, with the next unread
  * value where the bit is 1 and the all-zero pattern where it is 0.  Builds the

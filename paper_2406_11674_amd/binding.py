@@ -16,7 +16,7 @@ import numpy as np
 __all__ = [
     "EndorError", "Compressed", "DeviceMatrix", "lib", "library_path", "TILE_ELEMS", "MAX_BATCH",
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
-    "build_offsets", "decompress", "decompress_with_offsets",
+    "build_offsets", "build_offsets_host", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
     "decompress_rows", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, _i64, _i64, _p, _p, _i64, _p, _p]
+        L.endor_build_offsets_host.restype = ctypes.c_int
+        L.endor_build_offsets_host.argtypes = [_i64, _i64, _p, _p, _sz]
         L.endor_build_offsets.restype = ctypes.c_int
         L.endor_build_offsets.argtypes = [_i64, _i64, _p, _p, _sz, _p, _p]
         for name in ("endor_decompress", "endor_decompress_with_offsets",
@@ -150,6 +152,15 @@ def compress(dense: np.ndarray, want_row_offsets: bool = True) -> Compressed:
     _check(fn(W.ctypes.data, rows, cols, bitmap.ctypes.data, values.ctypes.data, values.size, ro,
               ctypes.byref(nnz)), "endor_compress")
     return Compressed(rows, cols, bitmap, values, row_offsets)
+
+
+def build_offsets_host(c: Compressed) -> np.ndarray:
+    """endor_build_offsets_host: the tile offset table as a host byte array, ready to be
+    copied to the device and passed as `workspace` to the *_with_offsets calls."""
+    ws = np.zeros(max(workspace_bytes(c.rows, c.cols), 256), dtype=np.uint8)
+    _check(lib().endor_build_offsets_host(c.rows, c.cols, c.bitmap.ctypes.data, ws.ctypes.data, ws.size),
+           "endor_build_offsets_host")
+    return ws
 
 
 # ------------------------------------------------------------------ device side

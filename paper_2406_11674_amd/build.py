@@ -20,7 +20,7 @@ FLAGS = [
     "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
     # packed-fp32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-I", os.path.join(ROOT, "include"),
+    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
 ]
 
 

@@ -9,6 +9,7 @@
 // value stream, pass 2 packs the values and samples the running count at every
 // row start.
 #include "endor.h"
+#include "endor_layout.h"
 
 #include <algorithm>
 #include <cstring>
@@ -21,13 +22,7 @@
 
 namespace {
 
-constexpr int64_t kMaxElems = int64_t(1) << 34;
-
-bool dims_ok(int64_t rows, int64_t cols) {
-    if (rows < 0 || cols < 0) return false;
-    if (rows == 0 || cols == 0) return true;
-    return cols <= (kMaxElems - 1) / rows;  // rows*cols < 2^34, without overflow
-}
+using endor_layout::dims_ok;
 
 // bit i of the result = (d[i] != 0), for 64 consecutive elements
 inline uint64_t nonzero_mask64(const uint16_t *d) {
@@ -215,4 +210,49 @@ extern "C" endor_status endor_compress_u8(const uint8_t *dense, int64_t rows, in
                                           uint8_t *bitmap, uint8_t *values, int64_t values_capacity,
                                           int64_t *row_offsets, int64_t *nnz_out) {
     return compress_impl<uint8_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+}
+
+// The tile offset table of a bitmap, built on the host in exactly the layout the device
+// kernels read (see endor_layout.h): the counter k of Algorithm 2 sampled every 4096
+// positions, stored per 256-tile chunk.
+extern "C" endor_status endor_build_offsets_host(int64_t rows, int64_t cols, const uint8_t *bitmap,
+                                                 void *workspace, size_t workspace_bytes) {
+    using namespace endor_layout;
+    if (rows < 0 || cols < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    const int64_t n = rows * cols;
+    if (n == 0) return ENDOR_OK;
+    if (!bitmap || !workspace) return ENDOR_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_bytes_n(n)) return ENDOR_ERR_BUFFER_TOO_SMALL;
+    const uint32_t nchunks = chunks_of(n);
+    std::memset(workspace, 0, workspace_bytes_n(n));
+    uint32_t *chunk_total = static_cast<uint32_t *>(workspace);
+    uint32_t *tile_off = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + chunk_total_bytes(n));
+    const int64_t full_words = n / 64;
+    const int tail_bits = static_cast<int>(n % 64);
+    unsigned hw = std::thread::hardware_concurrency();
+    const int nthreads = static_cast<int>(std::min<int64_t>(std::min<unsigned>(hw ? hw : 1, 64), nchunks));
+    run_threads(nthreads, [&](int t) {
+        for (uint32_t c = nchunks * uint64_t(t) / nthreads; c < nchunks * uint64_t(t + 1) / nthreads; ++c) {
+            uint32_t run = 0;
+            uint32_t *to = tile_off + size_t(c) * kChunkStride;
+            for (int tl = 0; tl < kTilesPerChunk; ++tl) {
+                to[tl] = run;
+                const int64_t w0 = (int64_t(c) * kTilesPerChunk + tl) * kTileWords;
+                for (int64_t w = w0; w < w0 + kTileWords; ++w) {
+                    uint64_t m = 0;
+                    if (w < full_words) {
+                        std::memcpy(&m, bitmap + 8 * w, 8);
+                    } else if (w == full_words && tail_bits) {
+                        std::memcpy(&m, bitmap + 8 * w, 8);
+                        m &= (uint64_t(1) << tail_bits) - 1;  // pad bits are ignored
+                    }
+                    run += static_cast<uint32_t>(__builtin_popcountll(m));
+                }
+            }
+            to[kTilesPerChunk] = run;
+            chunk_total[c] = run;
+        }
+    });
+    return ENDOR_OK;
 }

@@ -37,16 +37,19 @@
 #include <cstdint>
 
 #include "endor.h"
+#include "endor_layout.h"
 
 namespace {
 
-constexpr int kTileElems = ENDOR_TILE_ELEMS;  // flat positions per tile
-constexpr int kTileWords = kTileElems / 64;   // 64-bit bitmap words per tile (= lanes per wave)
-#ifndef ENDOR_TILES_PER_CHUNK
-#define ENDOR_TILES_PER_CHUNK 256
-#endif
-constexpr int kTilesPerChunk = ENDOR_TILES_PER_CHUNK;  // tiles one count workgroup covers
-constexpr int kChunkStride = kTilesPerChunk + 1;
+using endor_layout::kTileElems;      // flat positions per tile
+using endor_layout::kTileWords;      // 64-bit bitmap words per tile (= lanes per wave)
+using endor_layout::kTilesPerChunk;  // tiles one count workgroup covers
+using endor_layout::kChunkStride;
+using endor_layout::kMaxElems;
+using endor_layout::align256;
+using endor_layout::chunks_of;
+using endor_layout::dims_ok;
+using endor_layout::workspace_bytes_n;
 constexpr int kBlock = 256;                   // threads per workgroup of the row-offset kernel
 constexpr int kWaves = kBlock / 64;
 #ifndef ENDOR_COUNT_WAVES
@@ -74,7 +77,6 @@ constexpr int kExpandBlock = 64 * kExpandWaves;
 constexpr int kTilesPerWave = ENDOR_TILES_PER_WAVE;  // tiles one expand wave walks
 constexpr int kTilesPerBlock = kExpandWaves * kTilesPerWave;
 constexpr int kBlocksPerChunk = kTilesPerChunk / kTilesPerBlock;
-constexpr int64_t kMaxElems = int64_t(1) << 34;
 
 static_assert(kTileWords == 64, "one bitmap word per lane");
 static_assert(kCountBlock >= kTilesPerChunk && kCountTilesPerWave % 2 == 0 && kCountSteps >= 1,
@@ -838,24 +840,6 @@ __global__ __launch_bounds__(kBlock) void endor_row_offsets_kernel(MatParams M, 
 }
 
 // ---------------------------------------------------------------- host side
-
-size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
-
-bool dims_ok(int64_t rows, int64_t cols) {
-    if (rows < 0 || cols < 0) return false;
-    if (rows == 0 || cols == 0) return true;
-    return cols <= (kMaxElems - 1) / rows;
-}
-
-uint32_t chunks_of(int64_t n) {
-    const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
-    return static_cast<uint32_t>((ntiles + kTilesPerChunk - 1) / kTilesPerChunk);
-}
-
-size_t workspace_bytes_n(int64_t n) {
-    const size_t nc = chunks_of(n);
-    return align256(nc * sizeof(uint32_t)) + align256(nc * kChunkStride * sizeof(uint32_t));
-}
 
 struct Group {
     BatchParams P;

@@ -692,3 +692,22 @@ def test_more_than_2_pow_32_elements_sparse_random():
     rsel = endor.decompress_rows(m, ro, torch.from_numpy(sel).cuda())
     torch.cuda.synchronize()
     assert np.array_equal(rsel.cpu().numpy().view(np.uint16), expect)
+
+
+def test_host_built_offset_table_serves_the_device():
+    """The table built at compression time on the host, copied over, replaces the device pass."""
+    rows, cols = 1031, 2053
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=91, row_skew=True)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    host_ws = endor.build_offsets_host(c)
+    dev_ws, _ = endor.build_offsets(m)
+    torch.cuda.synchronize()
+    nchunks = ((rows * cols + 4095) // 4096 + 255) // 256
+    ct_bytes = (nchunks * 4 + 255) // 256 * 256
+    dev = dev_ws.cpu().numpy()
+    assert np.array_equal(dev[: nchunks * 4], host_ws[: nchunks * 4])
+    assert np.array_equal(dev[ct_bytes: ct_bytes + nchunks * 257 * 4], host_ws[ct_bytes: ct_bytes + nchunks * 257 * 4])
+    out = endor.decompress_with_offsets(m, torch.from_numpy(host_ws).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, c.values))

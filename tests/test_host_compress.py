@@ -120,3 +120,28 @@ def test_row_blocks_are_self_contained_blobs(rows, cols, nblocks):
         sub = orc.decompress(b.rows, cols, b.bitmap.numpy()[: endor.bitmap_bytes(b.rows, cols)],
                              b.values.numpy().view(np.uint16))
         assert np.array_equal(sub, w[b.row_begin:b.row_begin + b.rows])
+
+
+def _table_entries(ws: np.ndarray, n: int):
+    """Decode a workspace image (layout of the tile offset table) into absolute tile offsets."""
+    tile, per_chunk = 4096, 256
+    ntiles = (n + tile - 1) // tile
+    nchunks = (ntiles + per_chunk - 1) // per_chunk
+    ct_bytes = (nchunks * 4 + 255) // 256 * 256
+    chunk_total = ws[: nchunks * 4].view(np.uint32).astype(np.int64)
+    tile_off = ws[ct_bytes: ct_bytes + nchunks * 257 * 4].view(np.uint32).reshape(nchunks, 257).astype(np.int64)
+    base = np.concatenate([[0], np.cumsum(chunk_total)])[:-1]
+    absolute = (tile_off[:, :256] + base[:, None]).reshape(-1)[:ntiles]
+    assert np.array_equal(tile_off[:, 256], chunk_total)
+    return np.concatenate([absolute, [chunk_total.sum()]])
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 4096), (1, 4097), (300, 4099), (1031, 2053), (257, 4096), (600, 4096)], ids=str)
+def test_host_built_offset_table_matches_oracle(shape):
+    rows, cols = shape
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=rows + cols, row_skew=True)
+    c = endor.compress(w)
+    c.bitmap[-1] |= 0x80 if (rows * cols) % 64 else 0     # a pad bit must not be counted
+    ws = endor.build_offsets_host(c)
+    expect = orc.tile_offsets(rows * cols, 4096, c.bitmap)
+    assert np.array_equal(_table_entries(ws, rows * cols), expect)

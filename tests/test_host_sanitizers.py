@@ -19,6 +19,7 @@ def test_compressor_and_oracle_under_asan_ubsan(tmp_path):
     subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-pthread", "-fsanitize=address,undefined",
                            "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
                            "-I", os.path.join(ROOT, "include"),
+                           "-I", os.path.join(ROOT, "paper_2406_11674_amd", "csrc"),
                            os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"),
                            os.path.join(ROOT, "paper_2406_11674_amd", "csrc", "endor_host.cpp"),
                            str(obj), "-o", str(exe)])
