@@ -204,6 +204,9 @@ endor_status endor_decompress_u8_with_offsets(int64_t rows, int64_t cols,
                                               uint8_t *d_dense, void *stream);
 endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, int count,
                                        void *d_workspace, size_t workspace_bytes, void *stream);
+endor_status endor_decompress_batch_u8_with_offsets(const endor_matrix_u8 *mats, int count,
+                                                    const void *d_workspace, size_t workspace_bytes,
+                                                    void *stream);
 
 /*
  * DEVICE.  Row-subset decompression: the selective load that Section 4.2 sketches for

@@ -80,7 +80,8 @@ def lib() -> ctypes.CDLL:
             f.restype = ctypes.c_int
             f.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _p]
         for name in ("endor_decompress_batch", "endor_build_offsets_batch",
-                     "endor_decompress_batch_with_offsets", "endor_decompress_batch_u8"):
+                     "endor_decompress_batch_with_offsets", "endor_decompress_batch_u8",
+                     "endor_decompress_batch_u8_with_offsets"):
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
@@ -296,9 +297,13 @@ def build_offsets_batch(mats, workspace=None, stream=None):
 
 
 def decompress_batch_with_offsets(mats, workspace, outs=None, stream=None):
+    eb = mats[0].elem_bytes
+    if any(m.elem_bytes != eb for m in mats):
+        raise ValueError("one batch holds one element width")
     if outs is None:
-        outs = [_new_dense(m.rows, m.cols, mats[0].bitmap.device) for m in mats]
-    _batch("endor_decompress_batch_with_offsets", mats, outs, workspace, stream)
+        outs = [_new_dense(m.rows, m.cols, mats[0].bitmap.device, eb) for m in mats]
+    _batch("endor_decompress_batch_with_offsets" if eb == 2 else "endor_decompress_batch_u8_with_offsets",
+           mats, outs, workspace, stream)
     return outs
 
 

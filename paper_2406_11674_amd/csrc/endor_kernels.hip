@@ -1067,6 +1067,13 @@ extern "C" endor_status endor_decompress_batch_u8(const endor_matrix_u8 *mats, i
                      true, true, 1);
 }
 
+extern "C" endor_status endor_decompress_batch_u8_with_offsets(const endor_matrix_u8 *mats, int count,
+                                                               const void *d_workspace, size_t workspace_bytes,
+                                                               void *stream) {
+    return run_batch(reinterpret_cast<const endor_matrix *>(mats), count, const_cast<void *>(d_workspace),
+                     workspace_bytes, stream, false, true, 1);
+}
+
 // ---------------------------------------------------------------- selected rows (Section 4.2)
 
 namespace {

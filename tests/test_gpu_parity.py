@@ -352,8 +352,10 @@ def test_u8_batch_and_table_reuse_full_size():
         assert np.array_equal(expect, w)
         assert np.array_equal(o.cpu().numpy(), expect)
     again = endor.decompress_with_offsets(mats[0], ws)   # matrix 0's table sits at the start of the batch workspace
+    both = endor.decompress_batch_with_offsets(mats, ws)
     torch.cuda.synchronize()
     assert torch.equal(again, outs[0])
+    assert all(torch.equal(a, b) for a, b in zip(both, outs))
 
 
 # ---------------------------------------------------------------------------
