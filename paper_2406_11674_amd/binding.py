@@ -386,6 +386,8 @@ def pin(c: Compressed):
     torch = _torch()
     bm = torch.empty(c.bitmap.size, dtype=torch.uint8, pin_memory=True)
     bm.numpy()[:] = c.bitmap
+    if c.values.dtype.itemsize != 2:
+        raise ValueError("the host-to-device pipeline takes 16-bit values")
     vals = torch.empty(c.values.size, dtype=torch.int16, pin_memory=True)
     vals.numpy()[:] = c.values.view(np.int16)
     return bm, vals
