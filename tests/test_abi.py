@@ -88,3 +88,41 @@ def test_header_is_valid_c99_and_cxx17(tmp_path):
     src_cpp.write_text(src_c.read_text())
     subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c",
                            str(src_cpp), "-o", str(tmp_path / "use_cpp.o")])
+
+
+def test_widened_entry_points_reject_bad_arguments_without_launching():
+    L = endor.lib()
+    fake, ws = 0x1000, 1 << 20
+    # row subset
+    assert L.endor_decompress_rows(4, 64, None, fake, 10, fake, fake, 2, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, None, fake, 2, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake, None, 2, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake, fake, 2, None, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake + 4, fake, 2, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake, fake, -1, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 4 * 64 + 1, fake, fake, 2, fake, None) == 1
+    assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake, fake, 0, None, None) == 0       # nothing selected
+    assert L.endor_decompress_rows_u8(4, 64, fake, fake + 1, 10, fake, fake + 4, 2, fake + 3, None) == 1   # misaligned sel
+    # fused product
+    assert L.endor_gemv_f16(4, 64, None, fake, 10, fake, fake, fake, None) == 1
+    assert L.endor_gemv_f16(4, 64, fake, fake, 10, None, fake, fake, None) == 1
+    assert L.endor_gemv_f16(4, 64, fake, fake, 10, fake, None, fake, None) == 1
+    assert L.endor_gemv_f16(4, 64, fake, fake, 10, fake, fake, None, None) == 1
+    assert L.endor_gemv_f16(4, 64, fake, fake, 10, fake, fake, fake + 2, None) == 1
+    assert L.endor_gemv_f16(0, 64, None, None, 0, None, None, None, None) == 0
+    # device compressor
+    assert L.endor_compress_device(4, 64, None, fake, fake, 256, fake, ws, None, fake, None) == 1
+    assert L.endor_compress_device(4, 64, fake, None, fake, 256, fake, ws, None, fake, None) == 1
+    assert L.endor_compress_device(4, 64, fake, fake, fake, 256, fake, ws, None, None, None) == 1
+    assert L.endor_compress_device(4, 64, fake, fake, None, 256, fake, ws, None, fake, None) == 1
+    assert L.endor_compress_device(4, 64, fake, fake, fake, 256, fake, 16, None, fake, None) == 2
+    assert L.endor_compress_device(4, 64, fake, fake, fake, -1, fake, ws, None, fake, None) == 1
+    assert L.endor_compress_device(1 << 20, 1 << 20, fake, fake, fake, 256, fake, ws, None, fake, None) == 3
+    # host table builder
+    assert L.endor_build_offsets_host(4, 64, None, fake, ws) == 1
+    assert L.endor_build_offsets_host(-1, 64, fake, fake, ws) == 1
+    assert L.endor_build_offsets_host(0, 64, None, None, 0) == 0
+    # pipeline
+    assert L.endor_h2d_decompress_pipeline(None, 2, fake, ws, fake, ws, fake, fake + 8) == 1
+    assert L.endor_h2d_decompress_pipeline(None, 0, None, 0, None, 0, None, None) == 0
+    assert endor.stage_bytes(4, 64, 10) == 256 + 256 and endor.stage_bytes(4, 64, 257) == 0
