@@ -252,6 +252,25 @@ endor_status endor_compress_device_u8(int64_t rows, int64_t cols, const uint8_t 
                                       int64_t *d_row_offsets, int64_t *d_nnz_out, void *stream);
 
 /*
+ * DEVICE.  Column-subset decompression, the other half of Section 4.2's selective load (the
+ * columns of a down projection that belong to active neurons): d_out is rows x nsel,
+ * d_out[i][q] = W[i][d_sel[q]].  One rank query per row and selected column, answered from
+ * the bitmap and d_row_offsets.  Columns may repeat and come in any order; an index outside
+ * [0, cols) leaves its output column untouched.  cols <= 2^19; rows*nsel < 2^34.
+ * d_sel, d_row_offsets: device int64 arrays.  No workspace.
+ */
+endor_status endor_decompress_cols(int64_t rows, int64_t cols,
+                                   const uint8_t *d_bitmap, const uint16_t *d_values, int64_t nnz,
+                                   const int64_t *d_row_offsets,
+                                   const int64_t *d_sel, int64_t nsel,
+                                   uint16_t *d_out, void *stream);
+endor_status endor_decompress_cols_u8(int64_t rows, int64_t cols,
+                                      const uint8_t *d_bitmap, const uint8_t *d_values, int64_t nnz,
+                                      const int64_t *d_row_offsets,
+                                      const int64_t *d_sel, int64_t nsel,
+                                      uint8_t *d_out, void *stream);
+
+/*
  * DEVICE.  Fused consumer: y = W x computed straight from the compressed form, without
  * writing the dense matrix (the batch-1 linear operation the paper's workload runs on the
  * decompressed weight, Section 3.1; computing on the sparse form is the direction of

@@ -18,7 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "build_offsets_host", "decompress", "decompress_with_offsets",
     "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
-    "decompress_rows", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
+    "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
@@ -85,7 +85,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_p, ctypes.c_int, _p, _sz, _p]
-        for name in ("endor_decompress_rows", "endor_decompress_rows_u8"):
+        for name in ("endor_decompress_rows", "endor_decompress_rows_u8",
+                     "endor_decompress_cols", "endor_decompress_cols_u8"):
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _i64, _p, _p]
@@ -318,6 +319,20 @@ def decompress_rows(m: DeviceMatrix, row_offsets, sel, out=None, stream=None):
     fn = lib().endor_decompress_rows if m.elem_bytes == 2 else lib().endor_decompress_rows_u8
     _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets), _dptr(sel),
               nsel, _dptr(out), _stream_handle(stream)), "endor_decompress_rows")
+    return out
+
+
+def decompress_cols(m: DeviceMatrix, row_offsets, sel, out=None, stream=None):
+    """endor_decompress_cols[_u8]: out[i][q] = W[i][sel[q]].  row_offsets, sel: int64 device tensors."""
+    torch = _torch()
+    if row_offsets.dtype != torch.int64 or sel.dtype != torch.int64:
+        raise ValueError("row_offsets and sel must be int64 tensors")
+    nsel = int(sel.numel())
+    if out is None:
+        out = _new_dense(m.rows, nsel, m.bitmap.device, m.elem_bytes)
+    fn = lib().endor_decompress_cols if m.elem_bytes == 2 else lib().endor_decompress_cols_u8
+    _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets), _dptr(sel),
+              nsel, _dptr(out), _stream_handle(stream)), "endor_decompress_cols")
     return out
 
 

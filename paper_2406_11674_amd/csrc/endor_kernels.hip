@@ -531,6 +531,85 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
     expand_tile<E>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend, sink);
 }
 
+// ---------------------------------------------------------------- kernel 2c: selected columns
+
+struct ColsParams {
+    const uint64_t *bitmap;
+    const void *values;
+    void *out;                   // rows x nsel
+    const int64_t *row_offsets;  // rows + 1
+    const int64_t *sel;          // nsel column indices
+    int64_t rows, cols, nnz, nsel;
+};
+
+// 64 bits of row-aligned "virtual word" k of a row that starts at bit row_bit: bits
+// row_bit + 64k .. +63, clipped to the row's `cols` bits and to the bitmap.
+__device__ __forceinline__ uint64_t row_word(const uint64_t *bitmap, int64_t nwords, int64_t row_bit,
+                                             int64_t cols, int64_t k) {
+    const int64_t e = row_bit + 64 * k;
+    const int64_t w0 = e >> 6;
+    const uint32_t bs = static_cast<uint32_t>(e & 63);
+    uint64_t word = (w0 < nwords ? bitmap[w0] : 0) >> bs;
+    if (bs != 0) word |= (w0 + 1 < nwords ? bitmap[w0 + 1] : 0) << (64 - bs);
+    const int64_t rem = cols - 64 * k;
+    if (rem < 64) word &= (uint64_t(1) << rem) - 1;
+    return word;
+}
+
+// Column-subset decompression (the other half of Section 4.2's selective load: the columns
+// of a down projection that belong to active neurons).  out[i][q] = W[i][sel[q]].  One
+// workgroup per row: it scans the popcounts of the row's 64-bit words into LDS (the rank
+// of every word start inside the row), then answers one rank query per selected column:
+// rank = row_offsets[i] + prefix[word] + popcount(bits of the word below the column).
+template <int E>
+__global__ __launch_bounds__(kBlock) void endor_gather_cols_kernel(ColsParams C) {
+    extern __shared__ uint32_t s_prefix[];  // [ceil(cols/64)] 1 bits of the row before each word
+    __shared__ uint32_t s_wave[kWaves];
+    __shared__ uint32_t s_carry;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    const int64_t i = blockIdx.x;
+    const int64_t nwords = (C.rows * C.cols + 63) >> 6;
+    const int64_t row_bit = i * C.cols;
+    const int64_t nvw = (C.cols + 63) >> 6;
+
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int64_t k0 = 0; k0 < nvw; k0 += kBlock) {
+        const int64_t k = k0 + threadIdx.x;
+        const uint32_t pc = k < nvw ? __popcll(row_word(C.bitmap, nwords, row_bit, C.cols, k)) : 0u;
+        const uint32_t incl = wave_inclusive_scan(pc);
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        uint32_t before = s_carry;
+        for (uint32_t v = 0; v < wave; ++v) before += s_wave[v];
+        if (k < nvw) s_prefix[k] = before + incl - pc;
+        __syncthreads();
+        if (threadIdx.x == kBlock - 1) s_carry = before + incl;
+        __syncthreads();
+    }
+
+    const uint64_t first = static_cast<uint64_t>(C.row_offsets[i]);
+    for (int64_t q = threadIdx.x; q < C.nsel; q += kBlock) {
+        const int64_t c = C.sel[q];
+        if (c < 0 || c >= C.cols) continue;  // an index outside the matrix leaves its output column untouched
+        const int64_t k = c >> 6;
+        const uint32_t b = static_cast<uint32_t>(c & 63);
+        const uint64_t w = row_word(C.bitmap, nwords, row_bit, C.cols, k);
+        uint32_t v = 0;
+        if ((w >> b) & 1) {
+            const uint64_t idx = first + s_prefix[k] + __popcll(w & ((uint64_t(1) << b) - 1));
+            if (idx < static_cast<uint64_t>(C.nnz))
+                v = (E == 2) ? uint32_t(static_cast<const uint16_t *>(C.values)[idx])
+                             : uint32_t(static_cast<const uint8_t *>(C.values)[idx]);
+        }
+        if (E == 2)
+            static_cast<uint16_t *>(C.out)[i * C.nsel + q] = static_cast<uint16_t>(v);
+        else
+            static_cast<uint8_t *>(C.out)[i * C.nsel + q] = static_cast<uint8_t>(v);
+    }
+}
+
 // ---------------------------------------------------------------- fused consumer: y = W x
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -1248,4 +1327,60 @@ extern "C" endor_status endor_gemv_f16(int64_t rows, int64_t cols, const uint8_t
                        static_cast<hipStream_t>(stream), G);
     if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
     return ENDOR_OK;
+}
+
+// ---------------------------------------------------------------- selected columns (Section 4.2)
+
+namespace {
+
+constexpr int64_t kMaxGatherCols = int64_t(1) << 19;  // the row's word prefixes live in LDS (4 bytes per 64 columns)
+
+endor_status run_cols(int elem_bytes, int64_t rows, int64_t cols, const uint8_t *d_bitmap, const void *d_values,
+                      int64_t nnz, const int64_t *d_row_offsets, const int64_t *d_sel, int64_t nsel, void *d_out,
+                      void *stream) {
+    if (rows < 0 || cols < 0 || nsel < 0 || nnz < 0) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    if (nsel == 0 || rows == 0 || cols == 0) return ENDOR_OK;
+    if (cols > kMaxGatherCols || rows > 0x7fffffff || nsel > kMaxElems / rows) return ENDOR_ERR_UNSUPPORTED;
+    const uintptr_t em = static_cast<uintptr_t>(elem_bytes - 1);
+    if (nnz > rows * cols) return ENDOR_ERR_INVALID_ARG;
+    if (!d_bitmap || (reinterpret_cast<uintptr_t>(d_bitmap) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (nnz > 0 && (!d_values || (reinterpret_cast<uintptr_t>(d_values) & em))) return ENDOR_ERR_INVALID_ARG;
+    if (!d_row_offsets || (reinterpret_cast<uintptr_t>(d_row_offsets) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (!d_sel || (reinterpret_cast<uintptr_t>(d_sel) & 7)) return ENDOR_ERR_INVALID_ARG;
+    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & em)) return ENDOR_ERR_INVALID_ARG;
+    ColsParams C;
+    C.bitmap = reinterpret_cast<const uint64_t *>(d_bitmap);
+    C.values = d_values;
+    C.out = d_out;
+    C.row_offsets = d_row_offsets;
+    C.sel = d_sel;
+    C.rows = rows;
+    C.cols = cols;
+    C.nnz = nnz;
+    C.nsel = nsel;
+    const size_t lds = static_cast<size_t>((cols + 63) / 64) * sizeof(uint32_t);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL((endor_gather_cols_kernel<2>), dim3(static_cast<unsigned>(rows)), dim3(kBlock), lds, s, C);
+    else
+        hipLaunchKernelGGL((endor_gather_cols_kernel<1>), dim3(static_cast<unsigned>(rows)), dim3(kBlock), lds, s, C);
+    if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    return ENDOR_OK;
+}
+
+}  // namespace
+
+extern "C" endor_status endor_decompress_cols(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                              const uint16_t *d_values, int64_t nnz,
+                                              const int64_t *d_row_offsets, const int64_t *d_sel, int64_t nsel,
+                                              uint16_t *d_out, void *stream) {
+    return run_cols(2, rows, cols, d_bitmap, d_values, nnz, d_row_offsets, d_sel, nsel, d_out, stream);
+}
+
+extern "C" endor_status endor_decompress_cols_u8(int64_t rows, int64_t cols, const uint8_t *d_bitmap,
+                                                 const uint8_t *d_values, int64_t nnz,
+                                                 const int64_t *d_row_offsets, const int64_t *d_sel,
+                                                 int64_t nsel, uint8_t *d_out, void *stream) {
+    return run_cols(1, rows, cols, d_bitmap, d_values, nnz, d_row_offsets, d_sel, nsel, d_out, stream);
 }

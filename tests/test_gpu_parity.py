@@ -713,3 +713,61 @@ def test_host_built_offset_table_serves_the_device():
     out = endor.decompress_with_offsets(m, torch.from_numpy(host_ws).cuda())
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, c.values))
+
+
+# ---------------------------------------------------------------------------
+# column-subset decompression (the down-projection half of Section 4.2's selective load)
+# ---------------------------------------------------------------------------
+COL_SHAPES = [(40, 77), (5, 3), (64, 64), (33, 4096), (17, 4097), (9, 12345), (300, 8192), (50, 28672), (7, 28673),
+              (3, 100000)]
+
+
+@pytest.mark.parametrize("shape", COL_SHAPES, ids=str)
+@pytest.mark.parametrize("wide", [True, False], ids=["fp16", "u8"])
+def test_decompress_cols_matches_oracle(shape, wide):
+    rows, cols = shape
+    _say(f"cols case shape={shape} wide={wide}")
+    if wide:
+        w = synth.pruned_fp16(rows, cols, 0.5, seed=rows + cols, row_skew=True)
+    else:
+        w = synth.pruned_int8(rows, cols, 0.4, seed=rows + cols)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    g = np.random.default_rng(cols)
+    sel_np = np.concatenate([g.integers(0, cols, size=max(1, cols // 3)), [cols - 1, 0, 0]]).astype(np.int64)
+    # the definition: Algorithm 2's output, then the selected columns of it
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)[:, sel_np]
+    out = torch.full((rows, sel_np.size), 0x5A, dtype=torch.int16 if wide else torch.uint8, device="cuda")
+    endor.decompress_cols(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda(), out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(expect.dtype), expect)
+
+
+def test_decompress_cols_out_of_range_index_is_skipped():
+    rows, cols = 12, 5000
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=79)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    sel_np = np.array([3, -1, cols, 4999], np.int64)
+    out = torch.full((rows, 4), POISON, dtype=torch.int16, device="cuda")
+    endor.decompress_cols(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda(), out=out)
+    torch.cuda.synchronize()
+    host = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(host[:, 0], w[:, 3]) and np.array_equal(host[:, 3], w[:, 4999])
+    assert np.all(host[:, 1] == POISON) and np.all(host[:, 2] == POISON)
+
+
+def test_decompress_cols_full_size_down_proj():
+    """A tenth of the columns of a Llama2-70B down projection (8192 x 28672), device-built row offsets."""
+    rows, cols = 8192, 28672
+    _say("cols full size")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=synth.seed_for(3, 6))
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    _, ro = endor.build_offsets(m, row_offsets=True)
+    sel_np = np.sort(np.random.default_rng(6).choice(cols, size=cols // 10, replace=False)).astype(np.int64)
+    out = endor.decompress_cols(m, ro, torch.from_numpy(sel_np).cuda())
+    torch.cuda.synchronize()
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    assert np.array_equal(expect, w)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), expect[:, sel_np])
