@@ -80,6 +80,21 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
           2 * sel_np.size * cols + sel_np.size * cols // 8 + 2 * nnz_sel,
           note="endor_decompress_rows on a sorted random tenth of the rows; bytes of the selected rows only")
 
+    # column subset on the widest matrix (the down projection): a tenth of the columns, sorted
+    wide = max(range(len(host)), key=lambda i: (host[i].cols, host[i].rows))
+    cw = host[wide]
+    mw = endor.to_device(cw) if wide != big else m
+    row = torch.from_numpy(cw.row_offsets).cuda()
+    csel_np = np.sort(np.random.default_rng(6).choice(cw.cols, size=max(1, cw.cols // 10), replace=False)).astype(np.int64)
+    csel = torch.from_numpy(csel_np).cuda()
+    ocol = torch.empty((cw.rows, csel_np.size), dtype=torch.int16, device="cuda")
+    timed("decompress_cols_10pct", lambda: endor.decompress_cols(mw, row, csel, out=ocol),
+          cw.rows * cw.cols // 8 + 2 * cw.rows * csel_np.size + 2 * (cw.nnz // 10),
+          note="endor_decompress_cols on a sorted random tenth of the columns of %s %dx%d; algorithmic = whole "
+               "bitmap + selected values read + output written (the values come 2 bytes at a time out of "
+               "32-byte sectors)" % (shapes[wide][0], cw.rows, cw.cols))
+    del ocol
+
     # device-side compressor: dense -> bitmap + values (+ table); two passes over the dense matrix by design
     dense = endor.decompress(m)
     vals = torch.empty(n, dtype=torch.int16, device="cuda")

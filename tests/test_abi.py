@@ -103,6 +103,12 @@ def test_widened_entry_points_reject_bad_arguments_without_launching():
     assert L.endor_decompress_rows(4, 64, fake, fake, 4 * 64 + 1, fake, fake, 2, fake, None) == 1
     assert L.endor_decompress_rows(4, 64, fake, fake, 10, fake, fake, 0, None, None) == 0       # nothing selected
     assert L.endor_decompress_rows_u8(4, 64, fake, fake + 1, 10, fake, fake + 4, 2, fake + 3, None) == 1   # misaligned sel
+    # column subset
+    assert L.endor_decompress_cols(4, 64, None, fake, 10, fake, fake, 2, fake, None) == 1
+    assert L.endor_decompress_cols(4, 64, fake, fake, 10, fake, None, 2, fake, None) == 1
+    assert L.endor_decompress_cols(4, 64, fake, fake, 10, fake, fake, 2, None, None) == 1
+    assert L.endor_decompress_cols(4, 1 << 20, fake, fake, 10, fake, fake, 2, fake, None) == 3   # row too long for LDS
+    assert L.endor_decompress_cols(4, 64, fake, fake, 10, fake, fake, 0, None, None) == 0
     # fused product
     assert L.endor_gemv_f16(4, 64, None, fake, 10, fake, fake, fake, None) == 1
     assert L.endor_gemv_f16(4, 64, fake, fake, 10, None, fake, fake, None) == 1
