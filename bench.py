@@ -119,6 +119,16 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
     timed("gemv_f16", lambda: endor.gemv_f16(m, ro, x, y=y), n // 8 + 2 * nnz + 8 * (rows + 1) + 2 * cols + 4 * rows,
           note="endor_gemv_f16: bitmap + values + row offsets + x read, y written; a dense fp16 GEMV "
                "would read %d bytes" % (2 * n))
+    # what the fused product replaces: decompress, then the library's dense fp16 matrix-vector product
+    dense16 = endor.decompress(m).view(torch.float16)
+    yd = torch.empty(rows, dtype=torch.float16, device="cuda")
+    ws1 = torch.empty(max(256, endor.workspace_bytes(rows, cols)), dtype=torch.uint8, device="cuda")
+    dbuf = torch.empty((rows, cols), dtype=torch.int16, device="cuda")
+    timed("reference_dense_mv", lambda: torch.mv(dense16, x, out=yd), 2 * n + 2 * cols + 2 * rows,
+          note="torch.mv on the already decompressed fp16 matrix (the vendor GEMV), for comparison")
+    timed("reference_decompress_then_mv",
+          lambda: (endor.decompress(m, out=dbuf, workspace=ws1), torch.mv(dbuf.view(torch.float16), x, out=yd)),
+          2 * n + n // 8 + 2 * nnz + 2 * n, note="endor_decompress followed by torch.mv: the unfused path")
     return out
 
 
