@@ -771,3 +771,32 @@ def test_decompress_cols_full_size_down_proj():
     expect = orc.decompress(rows, cols, c.bitmap, c.values)
     assert np.array_equal(expect, w)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), expect[:, sel_np])
+
+
+def test_concurrent_calls_on_two_streams_with_distinct_workspaces():
+    """The library keeps no state between calls: two host threads, two streams, two workspaces."""
+    import threading
+    cs = [endor.compress(synth.pruned_fp16(700, 4099, 0.5, seed=70 + i)) for i in range(2)]
+    mats = [endor.to_device(c) for c in cs]
+    outs = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in cs]
+    wss = [torch.empty(max(256, endor.workspace_bytes(c.rows, c.cols)), dtype=torch.uint8, device="cuda") for c in cs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            for _ in range(20):
+                endor.decompress(mats[i], out=outs[i], workspace=wss[i], stream=streams[i])
+        except Exception as e:  # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors
+    for c, o in zip(cs, outs):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), orc.decompress(c.rows, c.cols, c.bitmap, c.values))
