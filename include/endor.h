@@ -23,7 +23,8 @@
  *
  * CONVENTIONS.  Every function returns an endor_status (0 = ok); none throws,
  * aborts or prints.  The library never allocates, frees or keeps caller memory
- * and has no mutable global state.  "host" pointers are ordinary CPU memory;
+ * and has no mutable global state (one exception, stated there: the fixed
+ * device array of endor_decompress_batch_static).  "host" pointers are ordinary CPU memory;
  * "device" pointers are HIP device memory on the current device.  Device entry
  * points only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
  * default stream) and return without synchronising; argument errors are found
@@ -58,7 +59,7 @@ typedef int endor_status;
 enum {
     ENDOR_OK = 0,
     ENDOR_ERR_INVALID_ARG = 1,      /* NULL pointer, negative size, misaligned buffer, count out of range */
-    ENDOR_ERR_BUFFER_TOO_SMALL = 2, /* values_capacity or workspace_bytes too small */
+    ENDOR_ERR_BUFFER_TOO_SMALL = 2, /* values_capacity, workspace_bytes or the static scratch array too small */
     ENDOR_ERR_UNSUPPORTED = 3,      /* rows*cols >= 2^34 */
     ENDOR_ERR_HIP = 4               /* a HIP launch or API call failed */
 };
@@ -172,6 +173,24 @@ endor_status endor_build_offsets_batch(const endor_matrix *mats, int count,
 endor_status endor_decompress_batch_with_offsets(const endor_matrix *mats, int count,
                                                  const void *d_workspace, size_t workspace_bytes,
                                                  void *stream);
+
+/*
+ * DEVICE.  endor_decompress_batch for callers that cannot allocate device memory and have
+ * no workspace to pass: code running under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The offset tables go into a fixed array of
+ * ENDOR_STATIC_SCRATCH_BYTES bytes of device memory that is part of the library's code
+ * object (each GPU the library runs on holds its own copy until the process ends), so the
+ * call takes no workspace and performs no allocation of any kind; apart from resolving the
+ * array's address on its first call on a device it only enqueues the same two kernels as
+ * endor_decompress_batch.  Limit: the batch's endor_batch_workspace_bytes() must not exceed
+ * ENDOR_STATIC_SCRATCH_BYTES (about 4 * 2^30 elements in total), else
+ * ENDOR_ERR_BUFFER_TOO_SMALL and nothing is launched.  Every call on a GPU shares that GPU's
+ * array: calls that overlap in time on one GPU (different streams, or different host threads)
+ * race on it; calls on one stream are ordered and safe.  The array keeps the last call's
+ * tables; nothing in it needs clearing between calls.
+ */
+#define ENDOR_STATIC_SCRATCH_BYTES (4u << 20)
+endor_status endor_decompress_batch_static(const endor_matrix *mats, int count, void *stream);
 
 /*
  * 8-BIT ELEMENTS (Section 4.2, joint application with quantization): the same bitmap,

@@ -17,12 +17,13 @@ __all__ = [
     "EndorError", "Compressed", "DeviceMatrix", "lib", "library_path", "TILE_ELEMS", "MAX_BATCH",
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "build_offsets_host", "decompress", "decompress_with_offsets",
-    "decompress_batch", "build_offsets_batch", "decompress_batch_with_offsets",
+    "decompress_batch", "decompress_batch_static", "build_offsets_batch", "decompress_batch_with_offsets",
     "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
 ]
 
 TILE_ELEMS = 4096
 MAX_BATCH = 16
+STATIC_SCRATCH_BYTES = 4 << 20
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # ENDOR_LIBRARY points at another build of the same library (kernel tuning experiments)
 _LIB_PATH = os.environ.get("ENDOR_LIBRARY") or os.path.join(_HERE, "libendor.so")
@@ -94,6 +95,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_int
             f.argtypes = [_i64, _i64, _p, _p, _p, _i64, _p, _sz, _p, _p, _p]
+        L.endor_decompress_batch_static.restype = ctypes.c_int
+        L.endor_decompress_batch_static.argtypes = [_p, ctypes.c_int, _p]
         L.endor_gemv_f16.restype = ctypes.c_int
         L.endor_gemv_f16.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _p, _p]
         L.endor_stage_bytes.restype = _sz
@@ -288,6 +291,22 @@ def decompress_batch(mats, outs=None, workspace=None, stream=None):
         workspace = _new_workspace(batch_workspace_bytes(mats), dev)
     _batch("endor_decompress_batch" if eb == 2 else "endor_decompress_batch_u8", mats, outs, workspace, stream)
     return outs, workspace
+
+
+def decompress_batch_static(mats, outs, stream=None):
+    """endor_decompress_batch_static: the batch call that takes no workspace and allocates
+    nothing (its tables live in a fixed device array inside the library).  `outs` is required."""
+    if not mats:
+        return outs
+    eb = mats[0].elem_bytes
+    if eb != 2 or any(m.elem_bytes != eb for m in mats):
+        raise ValueError("decompress_batch_static takes 16-bit values")
+    if len(outs) != len(mats):
+        raise ValueError("one output per matrix")
+    arr = _descs(mats, outs)
+    _check(lib().endor_decompress_batch_static(ctypes.addressof(arr), len(mats), _stream_handle(stream)),
+           "endor_decompress_batch_static")
+    return outs
 
 
 def build_offsets_batch(mats, workspace=None, stream=None):

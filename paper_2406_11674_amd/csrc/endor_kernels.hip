@@ -35,6 +35,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "endor.h"
 #include "endor_layout.h"
@@ -1117,6 +1118,54 @@ extern "C" endor_status endor_build_offsets(int64_t rows, int64_t cols, const ui
     hipLaunchKernelGGL(endor_row_offsets_kernel, dim3(blocks), dim3(kBlock), 0, s, M, rows, cols, d_row_offsets);
     if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
     return ENDOR_OK;
+}
+
+// ---------------------------------------------------------------- no-allocation variant
+
+namespace {
+
+// The offset tables of endor_decompress_batch_static live here instead of in a caller's
+// workspace.  Every device the library runs on holds its own copy of the array at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, never
+// a device address.
+static __device__ __align__(256) unsigned char scratch[ENDOR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once known
+
+// Device address of `scratch` on the current device, resolved on the first call per device.
+endor_status static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return ENDOR_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return ENDOR_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ENDOR_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ENDOR_OK;
+}
+
+}  // namespace
+
+extern "C" endor_status endor_decompress_batch_static(const endor_matrix *mats, int count, void *stream) {
+    if (count < 0 || (count > 0 && !mats)) return ENDOR_ERR_INVALID_ARG;
+    if (count == 0) return ENDOR_OK;
+    for (int i = 0; i < count; ++i) {
+        if (mats[i].rows < 0 || mats[i].cols < 0) return ENDOR_ERR_INVALID_ARG;
+        if (!dims_ok(mats[i].rows, mats[i].cols)) return ENDOR_ERR_UNSUPPORTED;
+    }
+    const size_t need = endor_batch_workspace_bytes(mats, count);
+    if (need > size_t(ENDOR_STATIC_SCRATCH_BYTES)) return ENDOR_ERR_BUFFER_TOO_SMALL;
+    void *ws = nullptr;
+    const endor_status st = static_scratch(&ws);
+    if (st != ENDOR_OK) return st;
+    // Nothing in the table has to start at zero: the tile-offset kernel writes every entry
+    // of every chunk of this batch before the expand kernel reads it.
+    return run_batch(mats, count, ws, size_t(ENDOR_STATIC_SCRATCH_BYTES), stream, true, true);
 }
 
 // ---------------------------------------------------------------- 8-bit elements (Section 4.2)
