@@ -5,13 +5,24 @@ A step is one pass of the whole path over one batch of synthetic input: build th
 tile offset table from the bitmaps and expand every matrix of the workload into
 its dense fp16 form (endor_decompress_batch), inputs already resident in HBM.
 
-Prints ONE JSON line: dense GB/s produced (whole path), the roofline figures of
-the dominant kernel (the expand kernel, timed alone with HIP events on the stream
-it runs on) and the CPU oracle timed on the host cores as a reported baseline.
+Prints ONE JSON line.  Its headline (`value`, `roofline`, `cpu_baseline`) is the
+Llama2-70B decoder layer; beside it the same line carries
+  configs   every other benchmark configuration, measured the same way: the OPT-66B
+            attention projections and FFN pair, the FFN pair's host-to-device transfer
+            alone and overlapped with decompression, the down_proj keep sweep and the
+            row-skewed variant, the 1024x1024 case
+  extras    the entry points beyond plain decompression (8-bit values, row / column
+            subsets, device-side compressor, fused products), each against its own
+            algorithmic byte count
+  ceilings  plain streaming kernels (write, read, copy, the 1.125:2 mix) on the same
+            box: what the memory system delivers for traffic of this shape
+`--workload X --only` restricts the run to one workload (the form the rocprofv3
+summaries under profiles/ are made with).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -34,7 +45,190 @@ WORKLOADS = {
 }
 
 
-def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def make_inputs(endor, synth, workload, keep, row_skew, variant=0):
+    cfg, _ = WORKLOADS[workload]
+    host = []
+    for i, (_, rows, cols) in enumerate(synth.CONFIGS[cfg]):
+        w = synth.pruned_fp16(rows, cols, keep, seed=synth.seed_for(cfg, i, variant), row_skew=row_skew)
+        host.append(endor.compress(w, want_row_offsets=True))
+        del w
+    return host
+
+
+class Resident:
+    """A workload resident in HBM: `rotate` device copies of the compressed input (so that no
+    step finds its input in a cache left by the step before), one set of outputs."""
+
+    def __init__(self, endor, torch, host, rotate):
+        self.endor, self.torch, self.host = endor, torch, host
+        self.rotate = max(1, rotate)
+        self.sets = [[endor.to_device(c) for c in host] for _ in range(self.rotate)]
+        self.outs = [torch.empty((c.rows, c.cols), dtype=torch.int16, device="cuda") for c in host]
+        ws_bytes = max(256, endor.batch_workspace_bytes(self.sets[0]))
+        self.workspaces = [torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") for _ in range(self.rotate)]
+        self.stream = torch.cuda.current_stream()
+        self.turn = 0
+        self.elements = sum(c.rows * c.cols for c in host)
+        self.nnz = sum(c.nnz for c in host)
+        self.dense_bytes = 2 * self.elements
+        self.alg_bytes = 2 * self.elements + sum((c.rows * c.cols + 7) // 8 for c in host) + 2 * self.nnz
+
+    def step(self):
+        k = self.turn = (self.turn + 1) % self.rotate
+        self.endor.decompress_batch(self.sets[k], outs=self.outs, workspace=self.workspaces[k], stream=self.stream)
+
+    def expand_only(self):
+        k = self.turn = (self.turn + 1) % self.rotate
+        self.endor.decompress_batch_with_offsets(self.sets[k], self.workspaces[k], outs=self.outs, stream=self.stream)
+
+    def build_tables(self):
+        for k in range(self.rotate):
+            self.endor.build_offsets_batch(self.sets[k], workspace=self.workspaces[k], stream=self.stream)
+
+    def time_steps(self, steps, warmup):
+        """W warm-up steps, then exactly K timed steps.  Returns (wall ms/step, event ms/step)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        ev0, ev1 = _events(torch)
+        t0 = time.perf_counter()
+        ev0.record(self.stream)
+        for _ in range(steps):
+            self.step()
+        ev1.record(self.stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+    def time_expand(self, reps, warmup):
+        """The expand kernel alone, tables already in the workspaces (the *_with_offsets path: a
+        table built once, or shipped with the blob).  Returns (average over back-to-back launches,
+        sorted single-launch durations), HIP events on the launch stream."""
+        torch = self.torch
+        self.build_tables()
+        for _ in range(max(2, warmup)):
+            self.expand_only()
+        torch.cuda.synchronize()
+        evs = [_events(torch) for _ in range(reps)]
+        for a, b in evs:
+            a.record(self.stream)
+            self.expand_only()
+            b.record(self.stream)
+        torch.cuda.synchronize()
+        per = sorted(a.elapsed_time(b) for a, b in evs)
+        a, b = _events(torch)
+        a.record(self.stream)
+        for _ in range(reps):
+            self.expand_only()
+        b.record(self.stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps, per
+
+
+def config_entry(endor, synth, torch, workload, keep, row_skew, steps, warmup, rotate):
+    host = make_inputs(endor, synth, workload, keep, row_skew)
+    r = Resident(endor, torch, host, rotate)
+    wall_ms, ev_ms = r.time_steps(steps, warmup)
+    exp_ms, _ = r.time_expand(max(10, steps), warmup)
+    entry = {
+        "workload": workload, "keep": keep, "row_skew": row_skew,
+        "ms_per_step": round(wall_ms, 4), "ms_per_step_events": round(ev_ms, 4),
+        "dense_GBps": round(r.dense_bytes / wall_ms / 1e6, 1),
+        "algorithmic_bytes": r.alg_bytes,
+        "hbm_frac_whole_path": round(r.alg_bytes / wall_ms / 1e6 / HBM_PEAK_GBS, 4),
+        "ms_expand_with_offsets": round(exp_ms, 4),
+        "hbm_frac_with_offsets": round(r.alg_bytes / exp_ms / 1e6 / HBM_PEAK_GBS, 4),
+    }
+    return entry, host, r
+
+
+def overlap_leg(endor, torch, host, outs, nblocks, reps=5):
+    """Pinned host -> device copy of the compressed blobs, alone and overlapped with
+    decompression (two streams, three staging slots).  Link-bound by design: these figures
+    are reported beside `value`, never as it.  Every timed call is bracketed by a device
+    synchronisation, so no call's tail hides under the next call's copies."""
+    eb = host[0].values.dtype.itemsize
+    whole = [endor.pin(c) for c in host]
+    blocks, block_outs = [], []
+    for c, o in zip(host, outs):
+        for b in endor.row_blocks(c, nblocks):
+            blocks.append(b)
+            block_outs.append(o[b.row_begin:b.row_begin + b.rows])
+    s_copy, s_copy2, s_comp = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    compressed_bytes = sum(c.bitmap.nbytes + c.values.nbytes for c in host)
+    dense_bytes = sum(eb * c.rows * c.cols for c in host)
+    pipe = endor.Pipeline.for_blobs(whole + blocks, s_copy, s_comp)
+    pipe2 = endor.Pipeline.for_blobs(whole + blocks, s_copy, s_comp, copy_stream2=s_copy2)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        best, total = 1e9, 0.0
+        for _ in range(reps):
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t
+            best, total = min(best, dt), total + dt
+        return total / reps * 1e3, best * 1e3
+
+    dev = [torch.empty(b.keep.numel(), dtype=torch.uint8, device="cuda") for b in whole]
+    dense_pinned = [torch.empty((c.rows, c.cols), dtype=o.dtype, pin_memory=True) for c, o in zip(host, outs)]
+
+    def copy_only():
+        with torch.cuda.stream(s_copy):
+            for d, b in zip(dev, whole):
+                d.copy_(b.keep, non_blocking=True)
+
+    def dense_copy():   # what the uncompressed baseline would move over the same link
+        with torch.cuda.stream(s_copy):
+            for o, hp in zip(outs, dense_pinned):
+                o.copy_(hp, non_blocking=True)
+
+    vdt = torch.int16 if eb == 2 else torch.uint8
+    mats = []
+    for c, d in zip(host, dev):
+        nb = c.bitmap.size
+        mats.append(endor.DeviceMatrix(c.rows, c.cols, d[:nb], d[(nb + 255) // 256 * 256:].view(vdt), c.nnz))
+    ws = torch.empty(max(256, endor.batch_workspace_bytes(mats)), dtype=torch.uint8, device="cuda")
+    copy_only()
+    torch.cuda.synchronize()
+    ms_copy, ms_copy_min = timed(copy_only)
+    ms_dense_copy, _ = timed(dense_copy)
+    ms_dec, _ = timed(lambda: endor.decompress_batch(mats, outs=outs, workspace=ws, stream=s_comp))
+    one_block = max(blocks, key=lambda b: b.rows * b.cols)
+    ms_pipe_whole, ms_pipe_whole_min = timed(lambda: pipe.run(whole, outs))
+    ms_pipe_blocks, ms_pipe_blocks_min = timed(lambda: pipe.run(blocks, block_outs))
+    ms_pipe2_whole, _ = timed(lambda: pipe2.run(whole, outs))
+    ms_pipe2_blocks, ms_pipe2_blocks_min = timed(lambda: pipe2.run(blocks, block_outs))
+    pipe.close()
+    pipe2.close()
+    return {
+        "elem_bytes": eb, "compressed_bytes": compressed_bytes, "dense_bytes": dense_bytes,
+        "ms_decompress_alone": round(ms_dec, 3),
+        "ms_h2d_copy_compressed_alone": round(ms_copy, 3),
+        "ms_h2d_copy_dense_alone": round(ms_dense_copy, 3),
+        "h2d_GBps": round(compressed_bytes / ms_copy / 1e6, 1),
+        "ms_pipeline_whole_matrices": round(ms_pipe_whole, 3),
+        "ms_pipeline_row_blocks": round(ms_pipe_blocks, 3),
+        "ms_pipeline_whole_matrices_two_copy_streams": round(ms_pipe2_whole, 3),
+        "ms_pipeline_row_blocks_two_copy_streams": round(ms_pipe2_blocks, 3),
+        "min_ms": {"copy": round(ms_copy_min, 3), "pipeline_whole": round(ms_pipe_whole_min, 3),
+                   "pipeline_row_blocks": round(ms_pipe_blocks_min, 3),
+                   "pipeline_row_blocks_two_copy_streams": round(ms_pipe2_blocks_min, 3)},
+        "row_blocks_per_matrix": nblocks, "blobs": len(blocks),
+        "largest_block_fraction": round(one_block.rows * one_block.cols * eb / dense_bytes, 4),
+        "sum_copy_plus_decompress_ms": round(ms_copy + ms_dec, 3),
+        "dense_GBps_pcie_inclusive": round(dense_bytes / min(ms_pipe_whole, ms_pipe_blocks, ms_pipe2_blocks) / 1e6, 1),
+        "speedup_vs_dense_copy": round(ms_dense_copy / min(ms_pipe_whole, ms_pipe_blocks, ms_pipe2_blocks), 3),
+    }
+
+
+def extras_leg(endor, synth, torch, np, host, shapes, cfg, keep):
     """Timings of the entry points beyond plain decompression, each with its own
     algorithmic byte count (what the operation must move) against the 8 TB/s HBM peak."""
     big = max(range(len(host)), key=lambda i: host[i].rows * host[i].cols)
@@ -45,11 +239,11 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
     stream = torch.cuda.current_stream()
     out = []
 
-    def timed(name, fn, alg_bytes, reps=20, note=""):
+    def timed(name, fn, alg_bytes, reps=20, note="", matrix=None):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a, b = _events(torch)
         a.record(stream)
         for _ in range(reps):
             fn()
@@ -57,12 +251,12 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / reps
         gbs = alg_bytes / ms / 1e6
-        out.append({"name": name, "matrix": [shapes[big][0], rows, cols], "ms": round(ms, 4),
+        out.append({"name": name, "matrix": matrix or [shapes[big][0], rows, cols], "ms": round(ms, 4),
                     "algorithmic_bytes": int(alg_bytes), "GB/s": round(gbs, 1),
                     "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "note": note})
 
     # 8-bit variant, whole path (same bitmap density, one byte per value)
-    w8 = synth.pruned_int8(rows, cols, args.keep, seed=synth.seed_for(cfg, big, 8))
+    w8 = synth.pruned_int8(rows, cols, keep, seed=synth.seed_for(cfg, big, 8))
     c8 = endor.compress(w8, want_row_offsets=False)
     m8 = endor.to_device(c8)
     o8 = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
@@ -88,14 +282,16 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
     csel_np = np.sort(np.random.default_rng(6).choice(cw.cols, size=max(1, cw.cols // 10), replace=False)).astype(np.int64)
     csel = torch.from_numpy(csel_np).cuda()
     ocol = torch.empty((cw.rows, csel_np.size), dtype=torch.int16, device="cuda")
+    frac_sel = csel_np.size / cw.cols
+    lines_touched = 1.0 - (1.0 - frac_sel) ** 32      # a 64-byte line holds 32 values, each selected w.p. frac_sel
     timed("decompress_cols_10pct", lambda: endor.decompress_cols(mw, row, csel, out=ocol),
-          cw.rows * cw.cols // 8 + 2 * cw.rows * csel_np.size + 2 * (cw.nnz // 10),
-          note="endor_decompress_cols on a sorted random tenth of the columns of %s %dx%d; algorithmic = whole "
-               "bitmap + selected values read + output written (the values come 2 bytes at a time out of "
-               "32-byte sectors)" % (shapes[wide][0], cw.rows, cw.cols))
+          cw.rows * cw.cols // 8 + int(2 * cw.nnz * lines_touched) + 2 * cw.rows * csel_np.size,
+          matrix=[shapes[wide][0], cw.rows, cw.cols],
+          note="endor_decompress_cols on a sorted random tenth of the columns; algorithmic = bitmap + the 64-byte "
+               "lines of the value stream that hold a selected value (%.1f %% of them) + output" % (100 * lines_touched))
     del ocol
 
-    # device-side compressor: dense -> bitmap + values (+ table); two passes over the dense matrix by design
+    # device-side compressor: dense -> bitmap + values (+ table)
     dense = endor.decompress(m)
     vals = torch.empty(n, dtype=torch.int16, device="cuda")
     bm = torch.empty(endor.bitmap_bytes(rows, cols), dtype=torch.uint8, device="cuda")
@@ -108,12 +304,11 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
                                      ws.numel(), None, nnz_dev.data_ptr(), stream.cuda_stream)
         assert st == 0
     timed("compress_device", comp, 2 * n + n // 8 + 2 * nnz,
-          note="endor_compress_device; algorithmic = one read of dense + bitmap + values written "
-               "(the implementation reads the dense matrix twice)")
+          note="endor_compress_device; algorithmic = one read of dense + bitmap + values written")
     assert int(nnz_dev.item()) == nnz
     del dense, vals, bm
 
-    # fused consumer
+    # fused consumers
     x = torch.randn(cols, device="cuda").to(torch.float16)
     y = torch.empty(rows, dtype=torch.float32, device="cuda")
     timed("gemv_f16", lambda: endor.gemv_f16(m, ro, x, y=y), n // 8 + 2 * nnz + 8 * (rows + 1) + 2 * cols + 4 * rows,
@@ -132,74 +327,78 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, args):
     return out
 
 
-def overlap_leg(endor, torch, host, outs, args):
-    """Pinned host -> device copy of the compressed blobs, alone and overlapped with
-    decompression (two streams, double-buffered staging).  PCIe-bound by design: these
-    figures are reported beside `value`, never as it."""
-    pinned = [endor.pin(c) for c in host]
-    whole = [endor.HostBlob(c.rows, c.cols, p[0], p[1], c.nnz) for c, p in zip(host, pinned)]
-    blocks, block_outs = [], []
-    for c, p, o in zip(host, pinned, outs):
-        for b in endor.row_blocks(c, p, args.overlap_blocks):
-            blocks.append(b)
-            block_outs.append(o[b.row_begin:b.row_begin + b.rows])
-    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
-    compressed_bytes = sum(c.bitmap.nbytes + c.values.nbytes for c in host)
-    dense_bytes = sum(2 * c.rows * c.cols for c in host)
-
-    def buffers(blobs):
-        sb = max(endor.stage_bytes(b.rows, b.cols, b.nnz) for b in blobs)
-        wb = max(256, max(endor.workspace_bytes(b.rows, b.cols) for b in blobs))
-        return ([torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(2)],
-                [torch.empty(wb, dtype=torch.uint8, device="cuda") for _ in range(2)])
-
-    def timed(fn, reps=5):
-        fn()
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(reps):
+def ceilings_leg(torch, nbytes=1 << 30, reps=10):
+    """The streaming yardstick: plain kernels from libendor_probe.so, one 16-byte unit per
+    thread, timed with HIP events on the launch stream."""
+    path = os.path.join(ROOT, "paper_2406_11674_amd", "libendor_probe.so")
+    if not os.path.exists(path):
+        return None
+    P = ctypes.CDLL(path)
+    P.endor_probe_stream.restype = ctypes.c_int
+    P.endor_probe_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                     ctypes.c_void_p, ctypes.c_void_p]
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    res = {"bytes_per_launch": nbytes}
+    for kind, name, moved in ((0, "write", nbytes), (1, "read", nbytes), (2, "copy", 2 * nbytes),
+                              (3, "mix_1.125r_2w", nbytes + nbytes * 9 // 16)):
+        def fn():
+            rc = P.endor_probe_stream(kind, src.data_ptr(), dst.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream)
+            assert rc == 0
+        for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) / reps * 1e3
+        a, b = _events(torch)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        res[name] = {"ms": round(ms, 4), "GB/s": round(moved / ms / 1e6, 1),
+                     "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    return res
 
-    st_w, ws_w = buffers(whole)
-    st_b, ws_b = buffers(blocks)
-    dev_bm = [torch.empty(c.bitmap.size, dtype=torch.uint8, device="cuda") for c in host]
-    dev_v = [torch.empty(c.values.size, dtype=torch.int16, device="cuda") for c in host]
 
-    def copy_only():
-        with torch.cuda.stream(s_copy):
-            for (pb, pv), db, dv in zip(pinned, dev_bm, dev_v):
-                db.copy_(pb, non_blocking=True)
-                dv.copy_(pv, non_blocking=True)
-
-    def dense_copy():   # what the uncompressed baseline would move over the same link
-        with torch.cuda.stream(s_copy):
-            for o, hp in zip(outs, dense_pinned):
-                o.copy_(hp, non_blocking=True)
-
-    dense_pinned = [torch.empty((c.rows, c.cols), dtype=torch.int16, pin_memory=True) for c in host]
-    mats = [endor.DeviceMatrix(c.rows, c.cols, db, dv, c.nnz) for c, db, dv in zip(host, dev_bm, dev_v)]
-    ws = torch.empty(max(256, endor.batch_workspace_bytes(mats)), dtype=torch.uint8, device="cuda")
-    copy_only()
-    torch.cuda.synchronize()
-    ms_copy = timed(copy_only)
-    ms_dense_copy = timed(dense_copy)
-    ms_dec = timed(lambda: endor.decompress_batch(mats, outs=outs, workspace=ws, stream=s_comp), reps=20)
-    ms_pipe_whole = timed(lambda: endor.h2d_decompress_pipeline(whole, outs, st_w, ws_w, s_copy, s_comp))
-    ms_pipe_blocks = timed(lambda: endor.h2d_decompress_pipeline(blocks, block_outs, st_b, ws_b, s_copy, s_comp))
+def cpu_baseline(np, host, shapes, seconds):
+    """The oracle's Algorithm 2, rows split over the host threads (the analogue of the paper's
+    multi-core CPU decompression, Section 5.1), on a bounded sample: whole matrices of the
+    workload, largest first, until the budget is spent.  Output buffers are allocated and
+    touched before the clock starts."""
+    from oracle import endor_oracle as orc
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "1024")))
+    order = sorted(range(len(host)), key=lambda i: -host[i].rows * host[i].cols)
+    bufs = {}
+    for i in order:
+        key = (host[i].rows, host[i].cols)
+        if key not in bufs:
+            bufs[key] = np.zeros(key, np.uint16)
+    c0 = host[order[-1]]
+    orc.decompress_threaded(c0.rows, c0.cols, c0.bitmap, c0.values, c0.row_offsets, cores,
+                            out=bufs[(c0.rows, c0.cols)])       # load the library, start-up costs
+    done_bytes, spent, used, passes = 0, 0.0, [], 0
+    while spent * cores <= seconds and passes < 20:
+        passes += 1
+        for i in order:
+            c = host[i]
+            t = time.perf_counter()
+            orc.decompress_threaded(c.rows, c.cols, c.bitmap, c.values, c.row_offsets, cores,
+                                    out=bufs[(c.rows, c.cols)])
+            spent += time.perf_counter() - t
+            done_bytes += 2 * c.rows * c.cols
+            used.append(shapes[i][0])
+            if spent * cores > seconds:
+                break
     return {
-        "compressed_bytes": compressed_bytes, "dense_bytes": dense_bytes,
-        "ms_decompress_alone": round(ms_dec, 3),
-        "ms_h2d_copy_compressed_alone": round(ms_copy, 3),
-        "ms_h2d_copy_dense_alone": round(ms_dense_copy, 3),
-        "h2d_GBps": round(compressed_bytes / ms_copy / 1e6, 1),
-        "ms_pipeline_whole_matrices": round(ms_pipe_whole, 3),
-        "ms_pipeline_row_blocks": round(ms_pipe_blocks, 3),
-        "row_blocks_per_matrix": args.overlap_blocks,
-        "sum_copy_plus_decompress_ms": round(ms_copy + ms_dec, 3),
-        "dense_GBps_pcie_inclusive": round(dense_bytes / ms_pipe_blocks / 1e6, 1),
-        "speedup_vs_dense_copy": round(ms_dense_copy / ms_pipe_blocks, 3),
+        "value": round(done_bytes / spent / 1e9, 3),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"Algorithm 2 oracle, rows split over {cores} threads, {len(used)} whole matrices of the "
+                  f"workload, largest first, cycling ({done_bytes} dense bytes in {spent:.2f} s wall; output "
+                  f"buffers touched beforehand)",
     }
 
 
@@ -211,18 +410,21 @@ def main() -> int:
     ap.add_argument("--workload", default="llama2_70b_layer", choices=sorted(WORKLOADS))
     ap.add_argument("--keep", type=float, default=0.5)
     ap.add_argument("--row-skew", action="store_true")
+    ap.add_argument("--only", action="store_true",
+                    help="measure the chosen workload only: no configs / extras / ceilings / CPU baseline")
+    ap.add_argument("--no-configs", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough CPU-baseline budget (core-seconds)")
     ap.add_argument("--rotate", type=int, default=3,
                     help="number of distinct device copies of the compressed input that the timed steps "
                          "cycle through, so that no step finds its input in a cache left by the one before")
     ap.add_argument("--overlap", action="store_true",
-                    help="also time the pinned host-to-device copy, alone and pipelined with decompression "
-                         "on a second stream (adds an \"overlap\" object)")
+                    help="with --only: also time the pinned host-to-device copy, alone and pipelined with "
+                         "decompression on a second stream")
     ap.add_argument("--overlap-blocks", type=int, default=4, help="row blocks per matrix in the pipeline")
-    ap.add_argument("--extras", action="store_true",
-                    help="also time the widened entry points on the workload's largest matrix: 8-bit "
-                         "variant, row subset, device-side compressor, fused y = W x (adds an \"extras\" list)")
+    ap.add_argument("--extras", action="store_true", help="with --only: also time the widened entry points")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (a reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -242,96 +444,41 @@ def main() -> int:
         return 2
     endor.lib()  # fail loudly if the library is not built
     torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
+    full = not args.only
 
     cfg, desc = WORKLOADS[args.workload]
     shapes = synth.CONFIGS[cfg]
     t_gen = time.time()
-    host = []
-    for i, (name, rows, cols) in enumerate(shapes):
-        w = synth.pruned_fp16(rows, cols, args.keep, seed=synth.seed_for(cfg, i), row_skew=args.row_skew)
-        host.append(endor.compress(w, want_row_offsets=True))
-        del w
+    host = make_inputs(endor, synth, args.workload, args.keep, args.row_skew)
     t_gen = time.time() - t_gen
-
-    rotate = max(1, args.rotate)
-    mats_sets = [[endor.to_device(c, dev) for c in host] for _ in range(rotate)]
-    mats = mats_sets[0]
-    outs = [torch.empty((c.rows, c.cols), dtype=torch.int16, device=dev) for c in host]
-    ws_bytes = max(256, endor.batch_workspace_bytes(mats))
-    workspaces = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(rotate)]
-    stream = torch.cuda.current_stream()
-    turn = [0]
-
-    n_total = sum(c.rows * c.cols for c in host)
-    nnz_total = sum(c.nnz for c in host)
-    dense_bytes = 2 * n_total
-    alg_bytes = 2 * n_total + sum((c.rows * c.cols + 7) // 8 for c in host) + 2 * nnz_total
-
-    def step():
-        k = turn[0] = (turn[0] + 1) % rotate
-        endor.decompress_batch(mats_sets[k], outs=outs, workspace=workspaces[k], stream=stream)
-
-    def expand_only():
-        k = turn[0] = (turn[0] + 1) % rotate
-        endor.decompress_batch_with_offsets(mats_sets[k], workspaces[k], outs=outs, stream=stream)
+    res = Resident(endor, torch, host, args.rotate)
 
     if args.calibrate_copy:
         # a plain copy of the largest output into a same-sized buffer: reads and
         # writes exactly 2*rows*cols bytes, whatever the counters say about it
-        big = max(range(len(outs)), key=lambda i: outs[i].numel())
-        ref = torch.empty_like(outs[big])
-        ref.copy_(outs[big])
+        big = max(range(len(res.outs)), key=lambda i: res.outs[i].numel())
+        ref = torch.empty_like(res.outs[big])
+        ref.copy_(res.outs[big])
         torch.cuda.synchronize()
-        print(f"calibration copy: {2 * outs[big].numel()} bytes read and written", file=sys.stderr, flush=True)
+        print(f"calibration copy: {2 * res.outs[big].numel()} bytes read and written", file=sys.stderr, flush=True)
         del ref
 
     # ---- whole path: W warm-up steps, then exactly K timed steps
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(args.steps):
-        step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    wall_ms, ev_ms = res.time_steps(args.steps, args.warmup)
     ms_per_step = wall_ms
-    dense_gbs = dense_bytes / (ms_per_step * 1e-3) / 1e9
+    dense_gbs = res.dense_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- dominant kernel alone (every workspace holds its input set's table by now):
-    # per-launch duration from HIP events recorded around every launch
-    for k in range(rotate):
-        endor.build_offsets_batch(mats_sets[k], workspace=workspaces[k], stream=stream)
-    for _ in range(max(2, args.warmup)):
-        expand_only()
-    torch.cuda.synchronize()
-    reps = max(10, args.steps)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for a, b in evs:
-        a.record(stream)
-        expand_only()
-        b.record(stream)
-    torch.cuda.synchronize()
-    per = sorted(a.elapsed_time(b) for a, b in evs)
-    # back-to-back launches, one event pair around all of them: the average launch duration
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record(stream)
-    for _ in range(reps):
-        expand_only()
-    b.record(stream)
-    torch.cuda.synchronize()
-    expand_ms = a.elapsed_time(b) / reps
-    achieved = alg_bytes / (expand_ms * 1e-3) / 1e9
+    # ---- dominant kernel alone: per-launch duration from HIP events on the launch stream
+    expand_ms, per = res.time_expand(max(10, args.steps), args.warmup)
+    achieved = res.alg_bytes / (expand_ms * 1e-3) / 1e9
 
-    traffic = None
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
     if os.path.exists(tpath) and args.keep == 0.5 and not args.row_skew:
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
+        traffic_src = ("constant read from profiles/traffic_%s.json (rocprofv3 FETCH_SIZE + WRITE_SIZE runs of "
+                       "this command), not measured in this run" % args.workload)
 
     result = {
         "metric": "decompress throughput, dense GB/s and % of HBM roofline, Llama2-70B layer"
@@ -349,13 +496,16 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": args.workload, "description": desc, "keep": args.keep, "row_skew": args.row_skew,
-            "matrices": [[n, r, c] for n, r, c in shapes], "elements": n_total, "nnz": nnz_total,
-            "dense_bytes": dense_bytes, "algorithmic_bytes": alg_bytes, "input_sets_rotated": rotate,
+            "matrices": [[n, r, c] for n, r, c in shapes], "elements": res.elements, "nnz": res.nnz,
+            "dense_bytes": res.dense_bytes, "algorithmic_bytes": res.alg_bytes, "input_sets_rotated": res.rotate,
             "launch": "endor_decompress_batch: tile-offset kernel + expand kernel, one pair for the whole batch",
         },
         "path": {
             "ms_per_step_events": round(ev_ms, 4),
-            "hbm_frac_whole_path": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "hbm_frac_whole_path": round(res.alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "hbm_frac_with_offsets": round(achieved / HBM_PEAK_GBS, 4),
+            "with_offsets_note": "the table built once or shipped with the blob (endor_decompress_batch_with_offsets): "
+                                 "the expand kernel alone",
             "input_generation_s": round(t_gen, 1),
         },
         "roofline": {
@@ -366,46 +516,47 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
-            "bytes_per_launch": alg_bytes,
+            "traffic_source": traffic_src,
+            "bytes_per_launch": res.alg_bytes,
             "avg_launch_ms": round(expand_ms, 4),
             "median_single_launch_ms": round(per[len(per) // 2], 4),
             "min_single_launch_ms": round(per[0], 4),
         },
     }
 
-    if args.overlap:
-        result["overlap"] = overlap_leg(endor, torch, host, outs, args)
-    if args.extras:
-        result["extras"] = extras_leg(endor, synth, torch, np, host, shapes, cfg, args)
+    if args.only and args.overlap:
+        result["overlap"] = overlap_leg(endor, torch, host, res.outs, args.overlap_blocks)
+    if (args.only and args.extras) or (full and not args.no_extras):
+        result["extras"] = extras_leg(endor, synth, torch, np, host, shapes, cfg, args.keep)
+    if full and not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(np, host, shapes, args.cpu_seconds)
+    del res, host
+    torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline:
-        from oracle import endor_oracle as orc
-        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "1024")))
-        # bounded sample: the largest matrices of the workload, whole, until the budget is used
-        order = sorted(range(len(host)), key=lambda i: -host[i].rows * host[i].cols)
-        done_bytes, spent, used, passes = 0, 0.0, [], 0
-        while spent * cores <= args.cpu_seconds and passes < 20:
-            passes += 1
-            for i in order:
-                c = host[i]
-                buf = np.empty((c.rows, c.cols), np.uint16)
-                t = time.perf_counter()
-                orc.decompress_threaded(c.rows, c.cols, c.bitmap, c.values, c.row_offsets, cores, out=buf)
-                dt = time.perf_counter() - t
-                spent += dt
-                done_bytes += 2 * c.rows * c.cols
-                used.append(shapes[i][0])
-                del buf
-                if spent * cores > args.cpu_seconds:
-                    break
-        result["cpu_baseline"] = {
-            "value": round(done_bytes / spent / 1e9, 3),
-            "unit": "GB/s",
-            "cores": cores,
-            "kind": "oracle",
-            "sample": f"Algorithm 2 oracle, rows split over {cores} threads, {len(used)} whole matrices of the "
-                      f"workload, largest first, cycling ({done_bytes} dense bytes in {spent:.2f} s wall)",
-        }
+    if full and not args.no_configs:
+        csteps, cwarm = min(args.steps, 20), min(args.warmup, 3)
+        configs = []
+        for wl, keep, skew in (("1024sq", 0.5, False), ("opt66b_attn", 0.5, False), ("opt66b_ffn", 0.5, False),
+                               ("down_proj", 0.1, False), ("down_proj", 0.3, False), ("down_proj", 0.5, False),
+                               ("down_proj", 0.7, False), ("down_proj", 0.5, True)):
+            entry, chost, cres = config_entry(endor, synth, torch, wl, keep, skew, csteps, cwarm, args.rotate)
+            if wl == "opt66b_ffn":
+                entry["overlap"] = overlap_leg(endor, torch, chost, cres.outs, args.overlap_blocks)
+            configs.append(entry)
+            del chost, cres
+            torch.cuda.empty_cache()
+        # the 8-bit transfer (Sections 4.2 and 5.4): 9216x36864 int8 codes through the same pipeline
+        w8 = synth.pruned_int8(9216, 36864, 0.5, seed=synth.seed_for(2, 1, 8))
+        c8 = endor.compress(w8)
+        del w8
+        o8 = [torch.empty((c8.rows, c8.cols), dtype=torch.uint8, device="cuda")]
+        configs.append({"workload": "opt66b_fc2_int8", "keep": 0.5, "row_skew": False,
+                        "overlap": overlap_leg(endor, torch, [c8], o8, args.overlap_blocks)})
+        del c8, o8
+        torch.cuda.empty_cache()
+        result["configs"] = configs
+    if full and not args.no_ceilings:
+        result["ceilings"] = ceilings_leg(torch)
 
     print(json.dumps(result), flush=True)
     return 0

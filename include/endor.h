@@ -22,10 +22,16 @@
  * never inspects the values it places.
  *
  * CONVENTIONS.  Every function returns an endor_status (0 = ok); none throws,
- * aborts or prints.  The library never allocates, frees or keeps caller memory
- * and has no mutable global state (one exception, stated there: the fixed
- * device array of endor_decompress_batch_static).  "host" pointers are ordinary CPU memory;
- * "device" pointers are HIP device memory on the current device.  Device entry
+ * aborts or prints.  The library never allocates device memory and never frees
+ * or keeps caller memory; it has no mutable global state (one exception, stated
+ * there: the fixed device array of endor_decompress_batch_static).  The host
+ * entry points (endor_compress*, endor_build_offsets_host) use temporary host
+ * memory and worker threads and report ENDOR_ERR_HOST if they cannot get them;
+ * endor_pipeline_init creates HIP events, endor_pipeline_destroy releases them.
+ * "host" pointers are ordinary CPU memory; "device" pointers are memory the
+ * current HIP device can address: device memory, or pinned host memory from
+ * hipHostMalloc (the kernels then fetch the blob across the host link
+ * themselves: measured 54 GB/s against 57 GB/s for the copy engine).  Device entry
  * points only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
  * default stream) and return without synchronising; argument errors are found
  * on the host before anything is launched.  rows == 0 or cols == 0 is valid and
@@ -61,7 +67,9 @@ enum {
     ENDOR_ERR_INVALID_ARG = 1,      /* NULL pointer, negative size, misaligned buffer, count out of range */
     ENDOR_ERR_BUFFER_TOO_SMALL = 2, /* values_capacity, workspace_bytes or the static scratch array too small */
     ENDOR_ERR_UNSUPPORTED = 3,      /* rows*cols >= 2^34 */
-    ENDOR_ERR_HIP = 4               /* a HIP launch or API call failed */
+    ENDOR_ERR_HIP = 4,              /* a HIP launch or API call failed */
+    ENDOR_ERR_HOST = 5,             /* host memory or a host thread could not be obtained */
+    ENDOR_ERR_NNZ_MISMATCH = 6      /* written by endor_check_batch: nnz differs from the number of 1 bits */
 };
 
 /* Elements per tile of the device offset table (fixed; part of the workspace layout). */
@@ -304,48 +312,114 @@ endor_status endor_gemv_f16(int64_t rows, int64_t cols,
                             const uint16_t *d_x, float *d_y, void *stream);
 
 /*
+ * DEVICE.  Check mode (the end condition of Algorithm 2: its counter k must equal the
+ * number of packed values).  For each matrix of the batch, compare its nnz with the
+ * number of 1 bits of its bitmap as recorded in the offset tables that
+ * endor_decompress_batch / endor_build_offsets_batch wrote into d_workspace, and write
+ * ENDOR_OK or ENDOR_ERR_NNZ_MISMATCH to d_status[i] (device, `count` 32-bit words).  One
+ * small launch on `stream`, no synchronisation; the caller reads d_status whenever it next
+ * synchronises anyway.  Decompression of a blob with a wrong nnz is still memory-safe
+ * (values past nnz read as zero); this call is how a caller finds out.
+ */
+endor_status endor_check_batch(const endor_matrix *mats, int count,
+                               const void *d_workspace, size_t workspace_bytes,
+                               int32_t *d_status, void *stream);
+
+/*
  * HOST -> DEVICE transfer overlapped with decompression (the paper's inference-time
  * order for a CPU-mapped layer, Section 4.1 "Decompression": the compressed weight
  * is copied from host memory to GPU memory and decompressed there; Section 6 notes
  * that the smaller transfers make overlap with other GPU work worthwhile).
  *
- * One blob = one compressed matrix (or a block of whole rows of one, see below) in
- * HOST memory, preferably pinned (hipHostMalloc / torch pin_memory), and the device
- * address its dense form goes to.
+ * One blob = one compressed matrix (or a block of whole rows of one, see
+ * endor_row_block) in HOST memory, preferably pinned (hipHostMalloc / torch
+ * pin_memory), and the device address its dense form goes to.  elem_bytes is 2 for
+ * fp16 values and 1 for the 8-bit variant of Section 4.2 (whose transfer saving is
+ * what Section 5.4 measures).  If h_values lies exactly
+ * align256(endor_bitmap_bytes(rows, cols)) bytes after h_bitmap (align256 = round up to a
+ * multiple of 256), the blob crosses the link in one copy instead of two.
  */
 typedef struct endor_host_blob {
     int64_t rows;
     int64_t cols;
-    const uint8_t *h_bitmap;  /* host: endor_bitmap_bytes(rows, cols) bytes readable */
-    const uint16_t *h_values; /* host: nnz elements */
+    const uint8_t *h_bitmap; /* host: endor_bitmap_bytes(rows, cols) bytes readable */
+    const void *h_values;    /* host: nnz elements of elem_bytes bytes */
     int64_t nnz;
-    uint16_t *d_dense;        /* device out: rows*cols elements */
+    void *d_dense;           /* device out: rows*cols elements */
+    int32_t elem_bytes;      /* 2 or 1 */
+    int32_t reserved;        /* 0 */
 } endor_host_blob;
 
-/* Bytes of ONE device staging buffer able to hold this blob's bitmap and values
+/* Bytes of ONE device staging slot able to hold this blob's bitmap and values
  * (each rounded up to 256 bytes).  0 on bad arguments. */
-size_t endor_stage_bytes(int64_t rows, int64_t cols, int64_t nnz);
+size_t endor_stage_bytes(int64_t rows, int64_t cols, int64_t nnz, int elem_bytes);
 
 /*
- * Double-buffered pipeline over `count` blobs: on `copy_stream` blob k is copied into
- * staging buffer k%2 (hipMemcpyAsync) while `compute_stream` decompresses blob k-1 out
- * of the other buffer; events order copy -> decompress of the same blob and
- * decompress of blob k -> copy of blob k+2 into the buffer it frees.  Both streams must
- * be non-NULL, distinct and of default priority.  d_stage[b] must hold the largest
- * endor_stage_bytes of the blobs, d_workspace[b] the largest endor_workspace_bytes
- * (both 256-byte aligned, not in use by earlier unfinished work).  Returns after
- * enqueueing; the dense outputs are complete when compute_stream has drained.
- *
- * A matrix may be fed as several blobs of whole rows [r0, r1) for finer overlap:
- * rows = r1-r0, h_bitmap = bitmap + r0*cols/8 (needs r0*cols % 64 == 0),
- * h_values = values + row_offsets[r0], nnz = row_offsets[r1] - row_offsets[r0],
- * d_dense = dense + r0*cols.  The bits after the block's last row in its final bitmap
- * word belong to the next rows and are ignored, as pad bits are.
+ * HOST.  Row blocks: a matrix may be fed to the pipeline as several blobs of whole rows
+ * [r0, r1) for finer overlap.  endor_row_block_cuts chooses the block boundaries:
+ * `nblocks`+1 non-decreasing row indices from 0 to rows, each a multiple of the smallest
+ * row count whose bits fill whole 64-bit bitmap words (so every block's bitmap starts on a
+ * word boundary); blocks that come out empty are legal.  endor_row_block fills `out` for
+ * rows [r0, r1) of a compressed matrix in host memory: its bitmap starts at byte
+ * r0*cols/8 of the matrix's, its values at element row_offsets[r0], nnz =
+ * row_offsets[r1] - row_offsets[r0], d_dense = d_dense + r0*cols elements.  The bits
+ * after the block's last row in its final bitmap word belong to the next rows and are
+ * ignored by decompression, as pad bits are.  ENDOR_ERR_INVALID_ARG if r0*cols is not a
+ * multiple of 64 or the range is not inside the matrix.
  */
-endor_status endor_h2d_decompress_pipeline(const endor_host_blob *blobs, int count,
-                                           void *const d_stage[2], size_t stage_bytes,
-                                           void *const d_workspace[2], size_t workspace_bytes,
-                                           void *copy_stream, void *compute_stream);
+endor_status endor_row_block_cuts(int64_t rows, int64_t cols, int nblocks, int64_t *cuts);
+endor_status endor_row_block(int64_t rows, int64_t cols, int elem_bytes,
+                             const uint8_t *h_bitmap, const void *h_values,
+                             const int64_t *row_offsets, int64_t r0, int64_t r1,
+                             void *d_dense, endor_host_blob *out);
+
+/*
+ * The pipeline's state: three device staging slots and workspaces (caller-owned memory),
+ * two streams, and the events that order a slot's copy before its decompression and its
+ * decompression before the next copy into it.  The state lives across calls, so a call may
+ * follow an earlier one whose work is still running: the same events keep the slots safe.
+ * One endor_pipeline must not be used by two host threads at once.
+ */
+#define ENDOR_PIPELINE_SLOTS 3
+typedef struct endor_pipeline {
+    void *d_stage[ENDOR_PIPELINE_SLOTS];
+    void *d_workspace[ENDOR_PIPELINE_SLOTS];
+    size_t stage_bytes;
+    size_t workspace_bytes;
+    void *copy_stream;    /* hipStream_t */
+    void *copy_stream2;   /* hipStream_t or NULL: if set, blobs alternate between the two copy streams */
+    void *compute_stream; /* hipStream_t */
+    void *copied[ENDOR_PIPELINE_SLOTS]; /* hipEvent_t: the slot's blob has arrived */
+    void *freed[ENDOR_PIPELINE_SLOTS];  /* hipEvent_t: the slot's decompression has finished reading it */
+    uint32_t next_slot;
+    uint32_t slots_used;  /* bit b: freed[b] has been recorded at least once */
+    uint64_t blobs_done;  /* blobs enqueued so far */
+} endor_pipeline;
+
+/* Fill *p and create its six events (disable-timing).  copy_stream and compute_stream must
+ * be non-NULL; all streams distinct and of default priority.  copy_stream2 may be NULL.  With
+ * two copy streams consecutive blobs travel on alternating streams, so the next copy is
+ * already queued on a second copy engine when one ends (on MI355X consecutive copies on ONE
+ * stream leave the link idle for 20-50 us each time; whole matrices, few and large, do better
+ * on one stream, many row blocks on two).  Each d_stage[b] must hold stage_bytes bytes (the
+ * largest endor_stage_bytes of the blobs to come), each d_workspace[b] workspace_bytes
+ * (the largest endor_workspace_bytes); all 256-byte aligned and distinct. */
+endor_status endor_pipeline_init(endor_pipeline *p,
+                                 void *const d_stage[ENDOR_PIPELINE_SLOTS], size_t stage_bytes,
+                                 void *const d_workspace[ENDOR_PIPELINE_SLOTS], size_t workspace_bytes,
+                                 void *copy_stream, void *copy_stream2, void *compute_stream);
+
+/* Destroy the events.  Work already enqueued still completes. */
+endor_status endor_pipeline_destroy(endor_pipeline *p);
+
+/*
+ * Enqueue `count` blobs: on copy_stream blob k is copied into the next staging slot
+ * (hipMemcpyAsync) while compute_stream decompresses earlier blobs out of the other slots.
+ * Creates nothing, allocates nothing, and returns after enqueueing; the dense outputs are
+ * complete when compute_stream has drained.  Blobs larger than the slots are refused with
+ * ENDOR_ERR_BUFFER_TOO_SMALL before anything is enqueued.
+ */
+endor_status endor_h2d_decompress_pipeline(endor_pipeline *p, const endor_host_blob *blobs, int count);
 
 #ifdef __cplusplus
 }

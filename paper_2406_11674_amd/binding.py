@@ -18,15 +18,14 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "build_offsets_host", "decompress", "decompress_with_offsets",
     "decompress_batch", "decompress_batch_static", "build_offsets_batch", "decompress_batch_with_offsets",
-    "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "stage_bytes", "h2d_decompress_pipeline",
+    "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "row_block_cuts", "stage_bytes", "Pipeline", "PIPELINE_SLOTS", "check_batch",
 ]
 
 TILE_ELEMS = 4096
 MAX_BATCH = 16
 STATIC_SCRATCH_BYTES = 4 << 20
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# ENDOR_LIBRARY points at another build of the same library (kernel tuning experiments)
-_LIB_PATH = os.environ.get("ENDOR_LIBRARY") or os.path.join(_HERE, "libendor.so")
+_LIB_PATH = os.path.join(_HERE, "libendor.so")
 _lib = None
 
 _i64 = ctypes.c_int64
@@ -100,9 +99,19 @@ def lib() -> ctypes.CDLL:
         L.endor_gemv_f16.restype = ctypes.c_int
         L.endor_gemv_f16.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _p, _p]
         L.endor_stage_bytes.restype = _sz
-        L.endor_stage_bytes.argtypes = [_i64, _i64, _i64]
+        L.endor_stage_bytes.argtypes = [_i64, _i64, _i64, ctypes.c_int]
+        L.endor_row_block_cuts.restype = ctypes.c_int
+        L.endor_row_block_cuts.argtypes = [_i64, _i64, ctypes.c_int, _p]
+        L.endor_row_block.restype = ctypes.c_int
+        L.endor_row_block.argtypes = [_i64, _i64, ctypes.c_int, _p, _p, _p, _i64, _i64, _p, _p]
+        L.endor_pipeline_init.restype = ctypes.c_int
+        L.endor_pipeline_init.argtypes = [_p, _p, _sz, _p, _sz, _p, _p, _p]
+        L.endor_pipeline_destroy.restype = ctypes.c_int
+        L.endor_pipeline_destroy.argtypes = [_p]
         L.endor_h2d_decompress_pipeline.restype = ctypes.c_int
-        L.endor_h2d_decompress_pipeline.argtypes = [_p, ctypes.c_int, _p, _sz, _p, _sz, _p, _p]
+        L.endor_h2d_decompress_pipeline.argtypes = [_p, _p, ctypes.c_int]
+        L.endor_check_batch.restype = ctypes.c_int
+        L.endor_check_batch.argtypes = [_p, ctypes.c_int, _p, _sz, _p, _p]
         _lib = L
     return _lib
 
@@ -235,8 +244,8 @@ def decompress(m: DeviceMatrix, out=None, workspace=None, stream=None):
         out = _new_dense(m.rows, m.cols, m.bitmap.device, m.elem_bytes)
     if workspace is None:
         workspace = _new_workspace(workspace_bytes(m.rows, m.cols), m.bitmap.device)
-    if out.element_size() != m.elem_bytes:
-        raise ValueError("output element width differs from the values'")
+    if out.element_size() != m.elem_bytes or out.numel() != m.rows * m.cols:
+        raise ValueError("output must hold rows*cols elements of the values' width")
     fn = lib().endor_decompress if m.elem_bytes == 2 else lib().endor_decompress_u8
     _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(workspace),
               workspace.numel(), _dptr(out), _stream_handle(stream)), "endor_decompress")
@@ -246,8 +255,8 @@ def decompress(m: DeviceMatrix, out=None, workspace=None, stream=None):
 def decompress_with_offsets(m: DeviceMatrix, workspace, out=None, stream=None):
     if out is None:
         out = _new_dense(m.rows, m.cols, m.bitmap.device, m.elem_bytes)
-    if out.element_size() != m.elem_bytes:
-        raise ValueError("output element width differs from the values'")
+    if out.element_size() != m.elem_bytes or out.numel() != m.rows * m.cols:
+        raise ValueError("output must hold rows*cols elements of the values' width")
     fn = lib().endor_decompress_with_offsets if m.elem_bytes == 2 else lib().endor_decompress_u8_with_offsets
     _check(fn(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(workspace),
               workspace.numel(), _dptr(out), _stream_handle(stream)), "endor_decompress_with_offsets")
@@ -257,6 +266,8 @@ def decompress_with_offsets(m: DeviceMatrix, workspace, out=None, stream=None):
 def _descs(mats, outs):
     arr = (_Matrix * len(mats))()
     for i, m in enumerate(mats):
+        if outs is not None and (outs[i].numel() != m.rows * m.cols or outs[i].element_size() != m.elem_bytes):
+            raise ValueError("output %d does not have rows*cols elements of the values' width" % i)
         arr[i].rows, arr[i].cols = m.rows, m.cols
         arr[i].d_bitmap = _dptr(m.bitmap)
         arr[i].d_values = _dptr(m.values)
@@ -291,6 +302,18 @@ def decompress_batch(mats, outs=None, workspace=None, stream=None):
         workspace = _new_workspace(batch_workspace_bytes(mats), dev)
     _batch("endor_decompress_batch" if eb == 2 else "endor_decompress_batch_u8", mats, outs, workspace, stream)
     return outs, workspace
+
+
+def check_batch(mats, workspace, status=None, stream=None):
+    """endor_check_batch: status[i] = 0 if matrix i's nnz equals the number of 1 bits its table
+    records, else ENDOR_ERR_NNZ_MISMATCH (6).  Device int32 tensor; no synchronisation."""
+    torch = _torch()
+    if status is None:
+        status = torch.full((len(mats),), -1, dtype=torch.int32, device=mats[0].bitmap.device)
+    arr = _descs(mats, None)
+    _check(lib().endor_check_batch(ctypes.addressof(arr), len(mats), _dptr(workspace), workspace.numel(),
+                                   _dptr(status), _stream_handle(stream)), "endor_check_batch")
+    return status
 
 
 def decompress_batch_static(mats, outs, stream=None):
@@ -395,70 +418,143 @@ def gemv_f16(m: DeviceMatrix, row_offsets, x, y=None, stream=None):
 
 # ------------------------------------------------------------------ host -> device pipeline
 
+PIPELINE_SLOTS = 3
+
+
 class _HostBlob(ctypes.Structure):
     _fields_ = [("rows", _i64), ("cols", _i64), ("h_bitmap", _p), ("h_values", _p),
-                ("nnz", _i64), ("d_dense", _p)]
+                ("nnz", _i64), ("d_dense", _p), ("elem_bytes", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class _Pipeline(ctypes.Structure):
+    _fields_ = [("d_stage", _p * PIPELINE_SLOTS), ("d_workspace", _p * PIPELINE_SLOTS),
+                ("stage_bytes", _sz), ("workspace_bytes", _sz), ("copy_stream", _p), ("copy_stream2", _p),
+                ("compute_stream", _p), ("copied", _p * PIPELINE_SLOTS), ("freed", _p * PIPELINE_SLOTS),
+                ("next_slot", ctypes.c_uint32), ("slots_used", ctypes.c_uint32), ("blobs_done", ctypes.c_uint64)]
 
 
 @dataclass
 class HostBlob:
-    """A compressed matrix, or a block of whole rows of one, in (pinned) host tensors."""
+    """A compressed matrix, or a block of whole rows of one, inside a pinned host buffer."""
     rows: int
     cols: int
-    bitmap: object      # torch.uint8, host
-    values: object      # torch.int16, host
     nnz: int
+    elem_bytes: int
+    bitmap_ptr: int     # host address of the block's bitmap
+    values_ptr: int     # host address of the block's values
     row_begin: int = 0  # first row of the block inside its matrix
+    keep: object = None  # the pinned tensor(s) that own the memory
 
 
-def stage_bytes(rows: int, cols: int, nnz: int) -> int:
-    return int(lib().endor_stage_bytes(rows, cols, nnz))
+def stage_bytes(rows: int, cols: int, nnz: int, elem_bytes: int = 2) -> int:
+    return int(lib().endor_stage_bytes(rows, cols, nnz, elem_bytes))
 
 
-def pin(c: Compressed):
-    """Copy a Compressed into pinned host tensors (allocated pinned, not registered)."""
+def _align256(x: int) -> int:
+    return (x + 255) & ~255
+
+
+def pin(c: Compressed, pinned: bool = True):
+    """Copy a Compressed into ONE pinned host tensor (allocated pinned, not registered), the
+    values starting at the next multiple of 256 bytes after the bitmap, so that the pipeline
+    moves the blob in a single copy.  Returns a HostBlob.  pinned=False: ordinary host memory
+    (for use without a GPU)."""
     torch = _torch()
-    bm = torch.empty(c.bitmap.size, dtype=torch.uint8, pin_memory=True)
-    bm.numpy()[:] = c.bitmap
-    if c.values.dtype.itemsize != 2:
-        raise ValueError("the host-to-device pipeline takes 16-bit values")
-    vals = torch.empty(c.values.size, dtype=torch.int16, pin_memory=True)
-    vals.numpy()[:] = c.values.view(np.int16)
-    return bm, vals
+    eb = c.values.dtype.itemsize
+    bm_bytes = c.bitmap.size
+    buf = torch.empty(_align256(bm_bytes) + eb * c.values.size, dtype=torch.uint8, pin_memory=pinned)
+    flat = buf.numpy()
+    flat[:bm_bytes] = c.bitmap
+    flat[_align256(bm_bytes):] = c.values.view(np.uint8)
+    base = int(buf.data_ptr())
+    return HostBlob(c.rows, c.cols, c.nnz, eb, base, base + _align256(bm_bytes), 0, buf)
 
 
-def row_blocks(c: Compressed, pinned, nblocks: int):
-    """Split one matrix into up to `nblocks` HostBlobs of whole rows.  Block starts are
-    rounded so that r0*cols is a multiple of 64 (a bitmap word boundary); the block's
-    values start at row_offsets[r0]."""
-    bm, vals = pinned
+def row_block_cuts(rows: int, cols: int, nblocks: int):
+    """endor_row_block_cuts: nblocks + 1 row indices at bitmap word boundaries."""
+    cuts = (_i64 * (nblocks + 1))()
+    _check(lib().endor_row_block_cuts(rows, cols, nblocks, cuts), "endor_row_block_cuts")
+    return list(cuts)
+
+
+def row_blocks(c: Compressed, nblocks: int, pinned: bool = True):
+    """Split one matrix into HostBlobs of whole rows (endor_row_block_cuts / endor_row_block
+    decide where a block's bitmap and values start); each block is copied into a pinned
+    tensor of its own, bitmap and values adjacent as in pin()."""
+    torch = _torch()
     if c.row_offsets is None:
         raise ValueError("row_blocks needs the compressor's row offsets")
-    rows, cols = c.rows, c.cols
-    step = 64 // int(np.gcd(cols, 64)) if cols else 1   # smallest r with r*cols % 64 == 0
-    cuts = sorted({min(rows, (rows * i // nblocks) // step * step) for i in range(nblocks)} | {rows})
-    if cuts[0] != 0:
-        cuts.insert(0, 0)
+    eb = c.values.dtype.itemsize
+    bm8 = np.ascontiguousarray(c.bitmap)
+    v8 = np.ascontiguousarray(c.values).view(np.uint8)
+    ro = np.ascontiguousarray(c.row_offsets, dtype=np.int64)
+    cuts = row_block_cuts(c.rows, c.cols, nblocks)
     out = []
     for r0, r1 in zip(cuts[:-1], cuts[1:]):
         if r1 <= r0:
             continue
-        k0, k1 = int(c.row_offsets[r0]), int(c.row_offsets[r1])
-        out.append(HostBlob(r1 - r0, cols, bm[r0 * cols // 8:], vals[k0:k1], k1 - k0, r0))
+        blob = _HostBlob()
+        _check(lib().endor_row_block(c.rows, c.cols, eb, bm8.ctypes.data, v8.ctypes.data, ro.ctypes.data,
+                                     r0, r1, None, ctypes.byref(blob)), "endor_row_block")
+        bm_bytes = bitmap_bytes(blob.rows, blob.cols)
+        b_off = blob.h_bitmap - bm8.ctypes.data
+        v_off = (blob.h_values or v8.ctypes.data) - v8.ctypes.data
+        buf = torch.empty(_align256(bm_bytes) + eb * blob.nnz, dtype=torch.uint8, pin_memory=pinned)
+        flat = buf.numpy()
+        flat[:bm_bytes] = bm8[b_off:b_off + bm_bytes]
+        flat[_align256(bm_bytes):] = v8[v_off:v_off + eb * blob.nnz]
+        base = int(buf.data_ptr())
+        out.append(HostBlob(blob.rows, blob.cols, blob.nnz, eb, base, base + _align256(bm_bytes), r0, buf))
     return out
 
 
-def h2d_decompress_pipeline(blobs, outs, stages, workspaces, copy_stream, compute_stream):
-    """endor_h2d_decompress_pipeline.  `outs[k]`: device tensor (or view) that receives blob k."""
-    arr = (_HostBlob * len(blobs))()
-    for i, b in enumerate(blobs):
-        arr[i].rows, arr[i].cols, arr[i].nnz = b.rows, b.cols, b.nnz
-        arr[i].h_bitmap = _dptr(b.bitmap)
-        arr[i].h_values = _dptr(b.values)
-        arr[i].d_dense = _dptr(outs[i])
-    st = (_p * 2)(_dptr(stages[0]), _dptr(stages[1]))
-    ws = (_p * 2)(_dptr(workspaces[0]), _dptr(workspaces[1]))
-    _check(lib().endor_h2d_decompress_pipeline(
-        ctypes.addressof(arr), len(blobs), ctypes.addressof(st), min(s.numel() for s in stages),
-        ctypes.addressof(ws), min(w.numel() for w in workspaces),
-        int(copy_stream.cuda_stream), int(compute_stream.cuda_stream)), "endor_h2d_decompress_pipeline")
+class Pipeline:
+    """endor_pipeline: three staging slots and workspaces (torch tensors own the memory), two
+    torch streams, events created by endor_pipeline_init and destroyed with the object."""
+
+    def __init__(self, stage_bytes_: int, workspace_bytes_: int, copy_stream, compute_stream, device="cuda",
+                 copy_stream2=None):
+        torch = _torch()
+        self.stages = [torch.empty(max(256, stage_bytes_), dtype=torch.uint8, device=device)
+                       for _ in range(PIPELINE_SLOTS)]
+        self.workspaces = [torch.empty(max(256, workspace_bytes_), dtype=torch.uint8, device=device)
+                           for _ in range(PIPELINE_SLOTS)]
+        self.copy_stream, self.copy_stream2, self.compute_stream = copy_stream, copy_stream2, compute_stream
+        self._p = _Pipeline()
+        st = (_p * PIPELINE_SLOTS)(*[_dptr(t) for t in self.stages])
+        ws = (_p * PIPELINE_SLOTS)(*[_dptr(t) for t in self.workspaces])
+        _check(lib().endor_pipeline_init(ctypes.byref(self._p), st, self.stages[0].numel(), ws,
+                                         self.workspaces[0].numel(), int(copy_stream.cuda_stream),
+                                         int(copy_stream2.cuda_stream) if copy_stream2 is not None else None,
+                                         int(compute_stream.cuda_stream)), "endor_pipeline_init")
+        self._live = True
+
+    @classmethod
+    def for_blobs(cls, blobs, copy_stream, compute_stream, device="cuda", copy_stream2=None):
+        sb = max(stage_bytes(b.rows, b.cols, b.nnz, b.elem_bytes) for b in blobs)
+        wb = max(workspace_bytes(b.rows, b.cols) for b in blobs)
+        return cls(sb, wb, copy_stream, compute_stream, device, copy_stream2)
+
+    def run(self, blobs, outs):
+        """endor_h2d_decompress_pipeline.  `outs[k]`: device tensor (or view) that receives blob k."""
+        arr = (_HostBlob * len(blobs))()
+        for i, b in enumerate(blobs):
+            if outs[i].numel() != b.rows * b.cols or outs[i].element_size() != b.elem_bytes:
+                raise ValueError("output %d does not match its blob" % i)
+            arr[i].rows, arr[i].cols, arr[i].nnz = b.rows, b.cols, b.nnz
+            arr[i].h_bitmap, arr[i].h_values = b.bitmap_ptr, b.values_ptr
+            arr[i].d_dense = _dptr(outs[i])
+            arr[i].elem_bytes, arr[i].reserved = b.elem_bytes, 0
+        _check(lib().endor_h2d_decompress_pipeline(ctypes.byref(self._p), arr, len(blobs)),
+               "endor_h2d_decompress_pipeline")
+
+    def close(self):
+        if self._live:
+            self._live = False
+            _check(lib().endor_pipeline_destroy(ctypes.byref(self._p)), "endor_pipeline_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

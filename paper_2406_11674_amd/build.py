@@ -14,6 +14,9 @@ LIB = os.path.join(HERE, "libendor.so")
 SOURCES = [os.path.join(HERE, "csrc", "endor_kernels.hip"),
            os.path.join(HERE, "csrc", "endor_pipeline.hip"),
            os.path.join(HERE, "csrc", "endor_host.cpp")]
+# the streaming yardstick kernels bench.py times beside the library (not part of the product path)
+PROBE_LIB = os.path.join(HERE, "libendor_probe.so")
+PROBE_SOURCES = [os.path.join(HERE, "csrc", "stream_probe.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
@@ -24,9 +27,9 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp, *SOURCES]
+def _compile(lib: str, sources, verbose: bool, extra_flags=()) -> str:
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp, *sources]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -36,8 +39,14 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + proc.stdout)
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    """libendor.so, and beside it libendor_probe.so (bench.py's streaming yardstick)."""
+    _compile(PROBE_LIB, PROBE_SOURCES, verbose)
+    return _compile(LIB, SOURCES, verbose, extra_flags)
 
 
 if __name__ == "__main__":

@@ -13,6 +13,9 @@
 
 #include <algorithm>
 #include <cstring>
+#include <new>
+#include <numeric>
+#include <system_error>
 #include <thread>
 #include <vector>
 
@@ -76,6 +79,8 @@ struct Range {
     int64_t base = 0;  // 1 bits before the range
 };
 
+// Run f(0) .. f(nthreads-1), each on a thread of its own where one can be had; parts whose
+// thread cannot be created run on the calling thread instead.
 template <class F>
 void run_threads(int nthreads, F &&f) {
     if (nthreads <= 1) {
@@ -84,9 +89,26 @@ void run_threads(int nthreads, F &&f) {
     }
     std::vector<std::thread> pool;
     pool.reserve(nthreads - 1);
-    for (int t = 1; t < nthreads; ++t) pool.emplace_back([&f, t] { f(t); });
+    int started = 1;
+    try {
+        for (; started < nthreads; ++started) pool.emplace_back([&f, t = started] { f(t); });
+    } catch (const std::system_error &) {
+        // no more threads: parts started .. nthreads-1 are done below
+    }
     f(0);
+    for (int t = started; t < nthreads; ++t) f(t);
     for (auto &th : pool) th.join();
+}
+
+// The extern "C" entry points must not let an exception out (std::bad_alloc from the
+// vectors, std::system_error from thread start-up).
+template <class F>
+endor_status no_throw(F &&f) {
+    try {
+        return f();
+    } catch (...) {
+        return ENDOR_ERR_HOST;
+    }
 }
 
 }  // namespace
@@ -98,6 +120,8 @@ extern "C" const char *endor_status_string(endor_status s) {
         case ENDOR_ERR_BUFFER_TOO_SMALL: return "buffer too small";
         case ENDOR_ERR_UNSUPPORTED: return "unsupported size";
         case ENDOR_ERR_HIP: return "HIP error";
+        case ENDOR_ERR_HOST: return "out of host memory or threads";
+        case ENDOR_ERR_NNZ_MISMATCH: return "nnz differs from the number of 1 bits";
         default: return "unknown status";
     }
 }
@@ -203,13 +227,17 @@ endor_status compress_impl(const T *dense, int64_t rows, int64_t cols, uint8_t *
 extern "C" endor_status endor_compress(const uint16_t *dense, int64_t rows, int64_t cols,
                                        uint8_t *bitmap, uint16_t *values, int64_t values_capacity,
                                        int64_t *row_offsets, int64_t *nnz_out) {
-    return compress_impl<uint16_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+    return no_throw([&] {
+        return compress_impl<uint16_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+    });
 }
 
 extern "C" endor_status endor_compress_u8(const uint8_t *dense, int64_t rows, int64_t cols,
                                           uint8_t *bitmap, uint8_t *values, int64_t values_capacity,
                                           int64_t *row_offsets, int64_t *nnz_out) {
-    return compress_impl<uint8_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+    return no_throw([&] {
+        return compress_impl<uint8_t>(dense, rows, cols, bitmap, values, values_capacity, row_offsets, nnz_out);
+    });
 }
 
 // The tile offset table of a bitmap, built on the host in exactly the layout the device
@@ -217,6 +245,7 @@ extern "C" endor_status endor_compress_u8(const uint8_t *dense, int64_t rows, in
 // positions, stored per 256-tile chunk.
 extern "C" endor_status endor_build_offsets_host(int64_t rows, int64_t cols, const uint8_t *bitmap,
                                                  void *workspace, size_t workspace_bytes) {
+    return no_throw([&]() -> endor_status {
     using namespace endor_layout;
     if (rows < 0 || cols < 0) return ENDOR_ERR_INVALID_ARG;
     if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
@@ -254,5 +283,45 @@ extern "C" endor_status endor_build_offsets_host(int64_t rows, int64_t cols, con
             chunk_total[c] = run;
         }
     });
+    return ENDOR_OK;
+    });
+}
+
+
+// ---------------------------------------------------------------- row blocks for the pipeline
+
+extern "C" endor_status endor_row_block_cuts(int64_t rows, int64_t cols, int nblocks, int64_t *cuts) {
+    if (rows < 0 || cols < 0 || nblocks < 1 || !cuts) return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    // smallest number of rows whose bits fill whole 64-bit words: 64 / gcd(cols, 64)
+    const int64_t step = cols > 0 ? 64 / std::gcd<int64_t>(cols, 64) : 1;
+    cuts[0] = 0;
+    for (int b = 1; b < nblocks; ++b) {
+        // rows*b < 2^34 * 2^31 fits 64 bits
+        const int64_t r = rows * b / nblocks / step * step;
+        cuts[b] = r < cuts[b - 1] ? cuts[b - 1] : r;
+    }
+    cuts[nblocks] = rows;
+    return ENDOR_OK;
+}
+
+extern "C" endor_status endor_row_block(int64_t rows, int64_t cols, int elem_bytes, const uint8_t *h_bitmap,
+                                        const void *h_values, const int64_t *row_offsets, int64_t r0, int64_t r1,
+                                        void *d_dense, endor_host_blob *out) {
+    if (!out || !row_offsets || rows < 0 || cols < 0 || (elem_bytes != 1 && elem_bytes != 2))
+        return ENDOR_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return ENDOR_ERR_UNSUPPORTED;
+    if (r0 < 0 || r1 < r0 || r1 > rows) return ENDOR_ERR_INVALID_ARG;
+    if ((r0 * cols) % 64 != 0) return ENDOR_ERR_INVALID_ARG;
+    const int64_t k0 = row_offsets[r0], k1 = row_offsets[r1];
+    if (k0 < 0 || k1 < k0) return ENDOR_ERR_INVALID_ARG;
+    out->rows = r1 - r0;
+    out->cols = cols;
+    out->h_bitmap = h_bitmap ? h_bitmap + r0 * cols / 8 : nullptr;
+    out->h_values = h_values ? static_cast<const char *>(h_values) + k0 * elem_bytes : nullptr;
+    out->nnz = k1 - k0;
+    out->d_dense = d_dense ? static_cast<char *>(d_dense) + r0 * cols * elem_bytes : nullptr;
+    out->elem_bytes = elem_bytes;
+    out->reserved = 0;
     return ENDOR_OK;
 }

@@ -51,38 +51,21 @@ using endor_layout::align256;
 using endor_layout::chunks_of;
 using endor_layout::dims_ok;
 using endor_layout::workspace_bytes_n;
-constexpr int kBlock = 256;                   // threads per workgroup of the row-offset kernel
+constexpr int kBlock = 256;                   // threads per workgroup of the row-offset and column kernels
 constexpr int kWaves = kBlock / 64;
-#ifndef ENDOR_COUNT_WAVES
-#define ENDOR_COUNT_WAVES 16
-#endif
-constexpr int kCountWaves = ENDOR_COUNT_WAVES;  // waves per workgroup of the tile-offset kernel
+// Launch shapes.  Both were settled by measurement on MI355X (Llama2-70B layer, half the
+// elements kept): the tile-offset kernel with 16 waves per 256-tile chunk, the expand kernel
+// with one single-wave workgroup per tile (wider workgroups, several tiles per wave and half
+// tiles per wave were all slower), non-temporal value loads and stores, cacheable bitmap loads.
+constexpr int kCountWaves = 16;               // waves per workgroup of the tile-offset kernel
 constexpr int kCountBlock = 64 * kCountWaves;
 constexpr int kCountTilesPerWave = kTilesPerChunk / kCountWaves;
 constexpr int kCountSteps = kCountTilesPerWave / 2;  // two tiles per step
-// expand kernel launch shape (tunable at build time)
-#ifndef ENDOR_EXPAND_WAVES
-#define ENDOR_EXPAND_WAVES 1
-#endif
-#ifndef ENDOR_TILES_PER_WAVE
-#define ENDOR_TILES_PER_WAVE 1
-#endif
-#ifndef ENDOR_NT_LOAD
-#define ENDOR_NT_LOAD 1  // 1: values are read once, stream them; the bitmap is read twice and stays cacheable
-#endif
-#ifndef ENDOR_NT_STORE
-#define ENDOR_NT_STORE 1
-#endif
-constexpr int kExpandWaves = ENDOR_EXPAND_WAVES;   // waves per expand workgroup
-constexpr int kExpandBlock = 64 * kExpandWaves;
-constexpr int kTilesPerWave = ENDOR_TILES_PER_WAVE;  // tiles one expand wave walks
-constexpr int kTilesPerBlock = kExpandWaves * kTilesPerWave;
-constexpr int kBlocksPerChunk = kTilesPerChunk / kTilesPerBlock;
 
 static_assert(kTileWords == 64, "one bitmap word per lane");
-static_assert(kCountBlock >= kTilesPerChunk && kCountTilesPerWave % 2 == 0 && kCountSteps >= 1,
+static_assert(kTilesPerChunk == 256 && kCountBlock >= kTilesPerChunk && kCountTilesPerWave % 2 == 0 &&
+                  kCountSteps >= 1,
               "the tile-offset workgroup scans one tile count per thread");
-static_assert(kTilesPerChunk % kTilesPerBlock == 0, "expand workgroups do not straddle chunks");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -259,11 +242,8 @@ struct alignas(16) WaveScratch {
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
 template <int E>
 __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
-#if ENDOR_NT_LOAD
+    // values are read once: streamed past the caches (the bitmap, read by both kernels, stays cacheable)
     if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-#else
-    if (p >= vbeg && p + 16 <= vend) return *reinterpret_cast<const u32x4 *>(p);
-#endif
     uint32_t d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int j = 0; j < 16 / E; ++j) {
@@ -302,11 +282,7 @@ struct StoreSink {
     uint32_t nvalid;  // elements of the tile that exist (<= 4096)
     u32x4 held[kBurst ? Shape<E>::kSteps : 1];
     __device__ __forceinline__ void put(uint32_t le, u32x4 d) const {
-#if ENDOR_NT_STORE
         __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + size_t(le) * E));
-#else
-        *reinterpret_cast<u32x4 *>(out + size_t(le) * E) = d;
-#endif
     }
     __device__ __forceinline__ void operator()(int k, uint32_t le, u32x4 d) {
         if (kAlignedOut && nvalid == kTileElems) {
@@ -416,41 +392,34 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, ui
 }
 
 template <int E, bool kAlignedOut, bool kBurst>
-__global__ __launch_bounds__(kExpandBlock) void endor_expand_kernel(BatchParams P) {
-    __shared__ WaveScratch<E> s_scratch[kExpandWaves];
-    const uint32_t gc = blockIdx.x / kBlocksPerChunk;
-    const uint32_t sub = blockIdx.x % kBlocksPerChunk;
+__global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
+    __shared__ WaveScratch<E> s_scratch;
+    const uint32_t gc = blockIdx.x / kTilesPerChunk;
+    const uint32_t tl = blockIdx.x % kTilesPerChunk;  // tile, relative to the chunk
     const MatParams &M = P.m[find_matrix(P, gc)];
     const uint32_t c = gc - M.chunk_begin;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane = threadIdx.x;
 
     const int64_t n = M.n;
     const int64_t ntiles = (n + kTileElems - 1) / kTileElems;
-    const uint32_t tl0 = sub * kTilesPerBlock + wave * kTilesPerWave;  // first tile, relative to the chunk
-    const int64_t tile0 = int64_t(c) * kTilesPerChunk + tl0;
-    if (tile0 >= ntiles) return;  // whole wave; the kernel has no workgroup barrier
+    const int64_t tile = int64_t(c) * kTilesPerChunk + tl;
+    if (tile >= ntiles) return;
 
     const int64_t full_words = n >> 6;
     const uint32_t tail_bits = static_cast<uint32_t>(n & 63);
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(M.values);
     const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(M.nnz);
-    const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl0;
+    const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl;
     const uint64_t base = chunk_base(M.chunk_total, c, lane);
-
-    for (int t = 0; t < kTilesPerWave; ++t) {
-        const int64_t tile = tile0 + t;
-        if (tile >= ntiles) break;
-        const uint32_t o0 = tile_off[t];
-        const uint32_t cnt = tile_off[t + 1] - o0;  // 1 bits in this tile
-        const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
-        const int64_t e0 = tile * kTileElems;
-        const int64_t left = n - e0;
-        StoreSink<E, kAlignedOut, kBurst> sink;
-        sink.out = reinterpret_cast<uint8_t *>(M.dense) + e0 * E;
-        sink.nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
-        expand_tile<E>(s_scratch[wave], lane, word, vbeg + E * (base + o0), cnt, vbeg, vend, sink);
-    }
+    const uint32_t o0 = tile_off[0];
+    const uint32_t cnt = tile_off[1] - o0;  // 1 bits in this tile
+    const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
+    const int64_t e0 = tile * kTileElems;
+    const int64_t left = n - e0;
+    StoreSink<E, kAlignedOut, kBurst> sink;
+    sink.out = reinterpret_cast<uint8_t *>(M.dense) + e0 * E;
+    sink.nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+    expand_tile<E>(s_scratch, lane, word, vbeg + E * (base + o0), cnt, vbeg, vend, sink);
 }
 
 // This lane's 64 bits of a segment of `nbits` (<= 4096) bits that starts at an arbitrary
@@ -507,17 +476,20 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
     const int64_t left = R.cols - int64_t(g) * kTileElems;
     const uint32_t nbits = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
 
-    // 1 bits of the row before this segment: words [row_bit>>6, e>>6], first and last partial
-    uint32_t before = 0;
+    // 1 bits of the row before this segment: words [row_bit>>6, e>>6], first and last partial.
+    // A lane's share stays below 2^28; the total may not fit 32 bits for very wide rows, so
+    // the two 16-bit halves are summed across the wave separately.
+    uint64_t before = 0;
     {
+        uint32_t part = 0;
         const int64_t wa = row_bit >> 6, wb = e >> 6;
         for (int64_t w = wa + lane; w <= wb; w += 64) {
             uint64_t x = w < nwords ? R.bitmap[w] : 0;
             if (w == wa) x &= ~uint64_t(0) << (row_bit & 63);
             if (w == wb) x &= (uint64_t(1) << (e & 63)) - 1;
-            before += __popcll(x);
+            part += __popcll(x);
         }
-        before = wave_sum(before);
+        before = uint64_t(wave_sum(part & 0xffffu)) + (uint64_t(wave_sum(part >> 16)) << 16);
     }
 
     const uint64_t word = segment_word(R.bitmap, nwords, e, nbits, lane);
@@ -888,6 +860,14 @@ __global__ __launch_bounds__(64) void endor_total_kernel(MatParams M, int64_t *_
     if (threadIdx.x == 0) *nnz_out = static_cast<int64_t>(total);
 }
 
+// Check mode: one wave per matrix compares nnz with the number of 1 bits the table records.
+__global__ __launch_bounds__(64) void endor_check_kernel(BatchParams P, int32_t *__restrict__ status) {
+    const MatParams &M = P.m[blockIdx.x];
+    const uint64_t total = chunk_base(M.chunk_total, M.nchunks, threadIdx.x);
+    if (threadIdx.x == 0)
+        status[M.chunk_begin] = total == static_cast<uint64_t>(M.nnz) ? ENDOR_OK : ENDOR_ERR_NNZ_MISMATCH;
+}
+
 // ---------------------------------------------------------------- kernel 3: row offsets
 
 // One wave per row start: rank(i*cols) = chunk start + tile offset + 1 bits of the
@@ -977,13 +957,13 @@ endor_status fill_group(const endor_matrix *mats, int count, int need, int elem_
 
 template <int E>
 void launch_expand(const Group &g, hipStream_t s) {
-    const dim3 grid(g.chunks * kBlocksPerChunk);
+    const dim3 grid(g.chunks * kTilesPerChunk);
     if (!g.aligned_out)
-        hipLaunchKernelGGL((endor_expand_kernel<E, false, false>), grid, dim3(kExpandBlock), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, false, false>), grid, dim3(64), 0, s, g.P);
     else if (g.nnz * 5 < g.elems)  // fewer than one element in five kept: store-dominated
-        hipLaunchKernelGGL((endor_expand_kernel<E, true, true>), grid, dim3(kExpandBlock), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, true, true>), grid, dim3(64), 0, s, g.P);
     else
-        hipLaunchKernelGGL((endor_expand_kernel<E, true, false>), grid, dim3(kExpandBlock), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, true, false>), grid, dim3(64), 0, s, g.P);
 }
 
 // The shared driver of every device entry point.  `mats` holds 16-bit typed pointers;
@@ -1078,6 +1058,46 @@ extern "C" endor_status endor_decompress_batch_with_offsets(const endor_matrix *
                                                             const void *d_workspace, size_t workspace_bytes,
                                                             void *stream) {
     return run_batch(mats, count, const_cast<void *>(d_workspace), workspace_bytes, stream, false, true);
+}
+
+extern "C" endor_status endor_check_batch(const endor_matrix *mats, int count, const void *d_workspace,
+                                          size_t workspace_bytes, int32_t *d_status, void *stream) {
+    if (count < 0 || (count > 0 && (!mats || !d_status))) return ENDOR_ERR_INVALID_ARG;
+    if (count == 0) return ENDOR_OK;
+    if (reinterpret_cast<uintptr_t>(d_status) & 3) return ENDOR_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i) {
+        if (mats[i].rows < 0 || mats[i].cols < 0 || mats[i].nnz < 0) return ENDOR_ERR_INVALID_ARG;
+        if (!dims_ok(mats[i].rows, mats[i].cols)) return ENDOR_ERR_UNSUPPORTED;
+    }
+    if (endor_batch_workspace_bytes(mats, count) != 0 &&
+        (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
+        return ENDOR_ERR_INVALID_ARG;
+    if (endor_batch_workspace_bytes(mats, count) > workspace_bytes) return ENDOR_ERR_BUFFER_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = const_cast<char *>(static_cast<const char *>(d_workspace));
+    size_t off = 0;
+    for (int b = 0; b < count; b += ENDOR_MAX_BATCH) {
+        const int nb = count - b < ENDOR_MAX_BATCH ? count - b : ENDOR_MAX_BATCH;
+        // one descriptor per matrix, empty ones included (they have no chunks and no 1 bits);
+        // chunk_begin carries the matrix's index inside the batch for the kernel
+        BatchParams P;
+        P.count = nb;
+        for (int i = 0; i < nb; ++i) {
+            const endor_matrix &m = mats[b + i];
+            const int64_t n = m.rows * m.cols;
+            MatParams &M = P.m[i];
+            M = MatParams{};
+            M.n = n;
+            M.nnz = m.nnz;
+            M.nchunks = n > 0 ? chunks_of(n) : 0;
+            M.chunk_total = reinterpret_cast<uint32_t *>(ws + off);
+            M.chunk_begin = static_cast<uint32_t>(b + i);
+            off += n > 0 ? workspace_bytes_n(n) : 0;
+        }
+        hipLaunchKernelGGL(endor_check_kernel, dim3(nb), dim3(64), 0, s, P, d_status);
+        if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
+    }
+    return ENDOR_OK;
 }
 
 extern "C" endor_status endor_decompress(int64_t rows, int64_t cols, const uint8_t *d_bitmap,

@@ -19,12 +19,9 @@
 
 namespace endor_layout {
 
-#ifndef ENDOR_TILES_PER_CHUNK
-#define ENDOR_TILES_PER_CHUNK 256
-#endif
 constexpr int kTileElems = ENDOR_TILE_ELEMS;
 constexpr int kTileWords = kTileElems / 64;
-constexpr int kTilesPerChunk = ENDOR_TILES_PER_CHUNK;
+constexpr int kTilesPerChunk = 256;  // chunk sizes of 64, 128 and 512 tiles measured no faster
 constexpr int kChunkStride = kTilesPerChunk + 1;
 constexpr int64_t kMaxElems = int64_t(1) << 34;
 

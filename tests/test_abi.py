@@ -129,6 +129,20 @@ def test_widened_entry_points_reject_bad_arguments_without_launching():
     assert L.endor_build_offsets_host(-1, 64, fake, fake, ws) == 1
     assert L.endor_build_offsets_host(0, 64, None, None, 0) == 0
     # pipeline
-    assert L.endor_h2d_decompress_pipeline(None, 2, fake, ws, fake, ws, fake, fake + 8) == 1
-    assert L.endor_h2d_decompress_pipeline(None, 0, None, 0, None, 0, None, None) == 0
+    assert L.endor_h2d_decompress_pipeline(None, None, 2) == 1
+    assert L.endor_pipeline_init(None, None, 0, None, 0, None, None, None) == 1
+    assert L.endor_pipeline_destroy(None) == 1
+    pipe = (ctypes.c_byte * 256)()      # zeroed: never initialised, so it holds no events
+    blob = (ctypes.c_byte * 64)()
+    assert L.endor_h2d_decompress_pipeline(pipe, blob, 1) == 1
+    assert L.endor_h2d_decompress_pipeline(pipe, None, 0) == 0
+    three = (ctypes.c_void_p * 3)(fake, fake + 256, fake + 512)
+    same = (ctypes.c_void_p * 3)(fake, fake, fake + 512)
+    assert L.endor_pipeline_init(pipe, three, ws, three, ws, fake, None, fake) == 1           # one stream for both
+    assert L.endor_pipeline_init(pipe, three, ws, three, ws, fake, fake, fake + 8) == 1       # second copy stream = first
+    assert L.endor_pipeline_init(pipe, same, ws, three, ws, fake, None, fake + 8) == 1        # a slot given twice
     assert endor.stage_bytes(4, 64, 10) == 256 + 256 and endor.stage_bytes(4, 64, 257) == 0
+    assert endor.stage_bytes(4, 64, 256, 1) == 256 + 256 and endor.stage_bytes(4, 64, 10, 3) == 0
+    # check mode
+    assert L.endor_check_batch(None, 1, fake, ws, fake, None) == 1
+    assert L.endor_check_batch(None, 0, None, 0, None, None) == 0

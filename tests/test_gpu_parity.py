@@ -239,48 +239,95 @@ def test_down_proj_row_skew():
 # ---------------------------------------------------------------------------
 # pinned host -> device copy overlapped with decompression (two streams)
 # ---------------------------------------------------------------------------
-def _pipeline_buffers(blobs):
-    sb = max(endor.stage_bytes(b.rows, b.cols, b.nnz) for b in blobs)
-    wb = max(max(endor.workspace_bytes(b.rows, b.cols) for b in blobs), 256)
-    stages = [torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    wss = [torch.empty(wb, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    return stages, wss
+def _expect(c):
+    return orc.decompress(c.rows, c.cols, c.bitmap, c.values)
 
 
 def test_h2d_pipeline_whole_matrices_matches_oracle():
-    shapes = [(300, 4099), (1031, 2053), (64, 4096), (1, 1), (777, 1000)]
+    shapes = [(300, 4099), (1031, 2053), (64, 4096), (1, 1), (777, 1000), (0, 7)]
     cs = [endor.compress(synth.pruned_fp16(r, c, 0.5, seed=40 + i)) for i, (r, c) in enumerate(shapes)]
-    blobs = []
-    for c in cs:
-        bm, vals = endor.pin(c)
-        blobs.append(endor.HostBlob(c.rows, c.cols, bm, vals, c.nnz))
+    blobs = [endor.pin(c) for c in cs]
     outs = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in cs]
-    stages, wss = _pipeline_buffers(blobs)
     s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs(blobs, s_copy, s_comp)
     torch.cuda.synchronize()
-    for _ in range(2):   # twice: staging buffers are reused across calls
-        endor.h2d_decompress_pipeline(blobs, outs, stages, wss, s_copy, s_comp)
+    pipe.run(blobs, outs)
     torch.cuda.synchronize()
     for c, o in zip(cs, outs):
-        assert np.array_equal(o.cpu().numpy().view(np.uint16), orc.decompress(c.rows, c.cols, c.bitmap, c.values))
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), _expect(c))
+    pipe.close()
+
+
+def test_h2d_pipeline_back_to_back_calls_keep_their_slots_apart():
+    """Two calls with different blobs and outputs of their own, no synchronisation between
+    them: the second call's copies reuse the staging slots of the first, whose decompressions
+    may still be running, so the events kept in the pipeline object must order them."""
+    shapes = [(900, 4099), (1031, 2053), (640, 4096), (1500, 3000), (777, 1000), (2048, 2048), (333, 4100)]
+    first = [endor.compress(synth.pruned_fp16(r, c, 0.5, seed=300 + i)) for i, (r, c) in enumerate(shapes)]
+    second = [endor.compress(synth.pruned_fp16(r, c, 0.5, seed=400 + i)) for i, (r, c) in enumerate(shapes)]
+    b1, b2 = [endor.pin(c) for c in first], [endor.pin(c) for c in second]
+    o1 = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in first]
+    o2 = [torch.full((c.rows, c.cols), POISON, dtype=torch.int16, device="cuda") for c in second]
+    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs(b1 + b2, s_copy, s_comp)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        pipe.run(b1, o1)
+        pipe.run(b2, o2)
+    torch.cuda.synchronize()
+    for c, o in zip(first + second, o1 + o2):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), _expect(c))
+    pipe.close()
 
 
 @pytest.mark.parametrize("shape,nblocks", [((2048, 4096), 8), ((1031, 2053), 5), ((96, 24), 3), ((333, 64), 50)])
-def test_h2d_pipeline_row_blocks_matches_oracle(shape, nblocks):
+@pytest.mark.parametrize("wide", [True, False], ids=["fp16", "u8"])
+def test_h2d_pipeline_row_blocks_matches_oracle(shape, nblocks, wide):
     rows, cols = shape
-    w = synth.pruned_fp16(rows, cols, 0.5, seed=50, row_skew=True)
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=50, row_skew=True) if wide else synth.pruned_int8(rows, cols, 0.4, seed=51)
     c = endor.compress(w)
-    blobs = endor.row_blocks(c, endor.pin(c), nblocks)
+    blobs = endor.row_blocks(c, nblocks)
     assert sum(b.rows for b in blobs) == rows and sum(b.nnz for b in blobs) == c.nnz
-    out = torch.full((rows, cols), POISON, dtype=torch.int16, device="cuda")
+    out = torch.full((rows, cols), POISON & 0x7F, dtype=torch.int16 if wide else torch.uint8, device="cuda")
     outs = [out[b.row_begin:b.row_begin + b.rows] for b in blobs]
-    stages, wss = _pipeline_buffers(blobs)
     s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs(blobs, s_copy, s_comp)
     torch.cuda.synchronize()
-    endor.h2d_decompress_pipeline(blobs, outs, stages, wss, s_copy, s_comp)
+    pipe.run(blobs, outs)
     torch.cuda.synchronize()
-    expect = orc.decompress(rows, cols, c.bitmap, c.values)
-    assert np.array_equal(out.cpu().numpy().view(np.uint16), expect) and np.array_equal(expect, w)
+    expect = _expect(c)
+    assert np.array_equal(out.cpu().numpy().view(w.dtype), expect) and np.array_equal(expect, w)
+    pipe.close()
+
+
+def test_h2d_pipeline_u8_whole_matrices():
+    """The 8-bit variant through the transfer pipeline (Section 4.2: same bitmap, one byte per value)."""
+    shapes = [(300, 4099), (1031, 2053), (64, 4096), (1, 1)]
+    cs = [endor.compress(synth.pruned_int8(r, c, 0.5, seed=60 + i)) for i, (r, c) in enumerate(shapes)]
+    blobs = [endor.pin(c) for c in cs]
+    assert all(b.elem_bytes == 1 for b in blobs)
+    outs = [torch.full((c.rows, c.cols), 0x7F, dtype=torch.uint8, device="cuda") for c in cs]
+    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs(blobs, s_copy, s_comp)
+    torch.cuda.synchronize()
+    pipe.run(blobs, outs)
+    pipe.run(blobs, outs)
+    torch.cuda.synchronize()
+    for c, o in zip(cs, outs):
+        assert np.array_equal(o.cpu().numpy(), _expect(c))
+    pipe.close()
+
+
+def test_h2d_pipeline_refuses_a_blob_larger_than_its_slots():
+    small = endor.pin(endor.compress(synth.pruned_fp16(8, 64, 0.5, seed=1)))
+    big = endor.pin(endor.compress(synth.pruned_fp16(512, 4096, 0.5, seed=2)))
+    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs([small], s_copy, s_comp)
+    out = torch.empty((512, 4096), dtype=torch.int16, device="cuda")
+    with pytest.raises(endor.EndorError) as e:
+        pipe.run([big], [out])
+    assert e.value.status == 2
+    pipe.close()
 
 
 # ---------------------------------------------------------------------------
@@ -588,14 +635,117 @@ def test_gemv_full_size(shape):
     m = endor.to_device(c)
     y = endor.gemv_f16(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(x16).cuda())
     torch.cuda.synchronize()
-    # oracle on a sample of rows (the whole product is 235 M double multiply-adds per matrix:
-    # affordable, but the sample keeps the suite short); every sampled row is checked in full
-    sample = np.unique(np.concatenate([[0, rows - 1], np.random.default_rng(3).integers(0, rows, 400)]))
-    dense = orc.decompress_selected_rows(cols, sample.astype(np.int64), c.row_offsets, c.bitmap, c.values)
-    sb, sv, _ = orc.compress(dense)
-    ref = orc.gemv_f16(sample.size, cols, sb, sv, x16)
-    err = np.abs(y.cpu().numpy().astype(np.float64)[sample] - ref)
-    assert np.all(err <= _gemv_tolerance(dense, x16, cols))
+    ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)          # every row
+    err = np.abs(y.cpu().numpy().astype(np.float64) - ref)
+    tol = np.concatenate([_gemv_tolerance(w[r0:r0 + 1024], x16, cols) for r0 in range(0, rows, 1024)])
+    assert np.all(err <= tol)
+
+
+# ---------------------------------------------------------------------------
+# precondition violations stay memory-safe; check mode reports them
+# ---------------------------------------------------------------------------
+def test_short_values_are_zero_extended_and_nothing_past_nnz_is_read():
+    """A blob whose nnz is smaller than the number of 1 bits (truncated values): the output
+    equals Algorithm 2 on the values extended with zeros, i.e. nothing at or past
+    values + nnz was read (there sit non-zero guard patterns), and the guard zones around the
+    output are intact."""
+    rows, cols = 700, 4099
+    c = _random_compressed(rows, cols, 0.5, seed=77, zero_values=False)
+    for short in (c.nnz - 1, c.nnz - 4097, c.nnz // 2, 5, 0):
+        _say(f"short values: nnz {c.nnz} -> {short}")
+        vals = torch.full((c.nnz + 64,), 0x5A5A, dtype=torch.int16, device="cuda")     # guard patterns behind
+        vals[:short] = torch.from_numpy(c.values[:short].view(np.int16)).cuda()
+        guard = 4096
+        buf = torch.full((rows * cols + 2 * guard,), POISON, dtype=torch.int16, device="cuda")
+        out = buf[guard:guard + rows * cols].view(rows, cols)
+        m = endor.DeviceMatrix(rows, cols, torch.from_numpy(c.bitmap).cuda(), vals[:short], short)
+        endor.decompress(m, out=out)
+        torch.cuda.synchronize()
+        padded = np.zeros(c.nnz, np.uint16)
+        padded[:short] = c.values[:short]
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, padded))
+        assert bool((buf[:guard] == POISON).all()) and bool((buf[guard + rows * cols:] == POISON).all())
+
+
+def test_foreign_offset_table_cannot_write_outside_the_output():
+    """decompress_with_offsets with the table of ANOTHER bitmap of the same shape (a stale
+    workspace): the result is meaningless but stays inside the output buffer, and a correct
+    call afterwards is unaffected."""
+    rows, cols = 1031, 2053
+    a = _random_compressed(rows, cols, 0.9, seed=81)
+    b = _random_compressed(rows, cols, 0.1, seed=82)
+    ma, mb = endor.to_device(a), endor.to_device(b)
+    ws_a, _ = endor.build_offsets(ma)
+    ws_b, _ = endor.build_offsets(mb)
+    guard = 8192
+    for m, ws_wrong, ws_right, c in ((mb, ws_a, ws_b, b), (ma, ws_b, ws_a, a)):
+        buf = torch.full((rows * cols + 2 * guard,), POISON, dtype=torch.int16, device="cuda")
+        out = buf[guard:guard + rows * cols].view(rows, cols)
+        endor.decompress_with_offsets(m, ws_wrong, out=out)
+        torch.cuda.synchronize()
+        assert bool((buf[:guard] == POISON).all()) and bool((buf[guard + rows * cols:] == POISON).all())
+        endor.decompress_with_offsets(m, ws_right, out=out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), _expect(c))
+        assert bool((buf[:guard] == POISON).all()) and bool((buf[guard + rows * cols:] == POISON).all())
+
+
+def test_check_mode_reports_a_wrong_nnz_without_synchronising():
+    shapes = [(64, 4096), (300, 4099), (0, 9), (1031, 2053), (5, 7)]
+    cs = [_random_compressed(r, c, 0.5, seed=500 + i) for i, (r, c) in enumerate(shapes)]
+    mats = [endor.to_device(c) for c in cs]
+    outs, ws = endor.decompress_batch(mats)
+    status = endor.check_batch(mats, ws)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0, 0, 0, 0]
+    # the same bitmaps with one count off by one and one by many (values shortened accordingly)
+    wrong = list(mats)
+    wrong[1] = endor.DeviceMatrix(mats[1].rows, mats[1].cols, mats[1].bitmap, mats[1].values[:-1], mats[1].nnz - 1)
+    wrong[3] = endor.DeviceMatrix(mats[3].rows, mats[3].cols, mats[3].bitmap, mats[3].values[:10], 10)
+    outs, ws = endor.decompress_batch(wrong)
+    status = endor.check_batch(wrong, ws)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 6, 0, 6, 0]
+    # more matrices than one launch group
+    many = [mats[4]] * 20 + [wrong[1]]
+    ws = endor.build_offsets_batch(many)
+    status = endor.check_batch(many, ws)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0] * 20 + [6]
+
+
+def test_batch_mixing_aligned_and_unaligned_outputs():
+    """One output of a batch that is not 16-byte aligned puts the whole launch group on the
+    element-wise store path; every matrix must still be exact."""
+    shapes = [(64, 4096), (300, 4099), (17, 33), (1031, 2053)]
+    cs = [_random_compressed(r, c, 0.5, seed=600 + i) for i, (r, c) in enumerate(shapes)]
+    mats = [endor.to_device(c) for c in cs]
+    bufs, outs = [], []
+    for i, c in enumerate(cs):
+        off = [0, 1, 0, 3][i]                       # elements: 0 = aligned, 1 and 3 = 2 and 6 bytes off
+        buf = torch.full((c.rows * c.cols + 16,), POISON, dtype=torch.int16, device="cuda")
+        bufs.append((buf, off))
+        outs.append(buf[off:off + c.rows * c.cols].view(c.rows, c.cols))
+    endor.decompress_batch(mats, outs=outs)
+    torch.cuda.synchronize()
+    for c, o, (buf, off) in zip(cs, outs, bufs):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), _expect(c))
+        assert bool((buf[:off] == POISON).all()) and bool((buf[off + c.rows * c.cols:] == POISON).all())
+
+
+def test_decompress_straight_from_pinned_host_memory():
+    """Pinned host memory is addressable by the device, so the blob may stay on the host and
+    the kernels fetch it across the link themselves (no staging copy)."""
+    rows, cols = 1031, 2053
+    c = endor.compress(synth.pruned_fp16(rows, cols, 0.5, seed=90))
+    blob = endor.pin(c)
+    nb = endor.bitmap_bytes(rows, cols)
+    m = endor.DeviceMatrix(rows, cols, blob.keep[:nb], blob.keep[(nb + 255) // 256 * 256:].view(torch.int16), c.nnz)
+    out = torch.full((rows, cols), POISON, dtype=torch.int16, device="cuda")
+    ws = torch.empty(endor.workspace_bytes(rows, cols), dtype=torch.uint8, device="cuda")
+    endor.decompress(m, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), _expect(c))
 
 
 # ---------------------------------------------------------------------------
@@ -652,9 +802,8 @@ def test_more_than_2_pow_32_values_all_bits_set():
 
 
 def test_more_than_2_pow_32_elements_sparse_random():
-    """N = 2^32 + 2^20, one element in eight kept at random.  Whole output against a
-    mask-scatter built with torch on the device, slab by slab; sampled rows (the first, the
-    last, those around flat index 2^32) against the oracle's Algorithm 2."""
+    """N = 2^32 + 2^20, one element in eight kept at random.  Whole output against the oracle's
+    Algorithm 2 and, slab by slab, against a mask-scatter built with torch on the device."""
     rows, cols = 4097, 1 << 20
     n = rows * cols
     _say(f"2^32 test: sparse random, n={n}")
@@ -685,11 +834,14 @@ def test_more_than_2_pow_32_elements_sparse_random():
         expect.masked_scatter_(mask, m.values[int(row_offs[r0]):int(row_offs[r1])])
         assert torch.equal(out[r0:r1], expect), f"rows {r0}..{r1}"
         del mask, expect
-    # sampled rows against the oracle
+    # the whole output against the oracle's Algorithm 2 (rows split over the host threads)
+    full = orc.decompress_threaded(rows, cols, bm, values, row_offs, 16)
+    got_all = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got_all, full)
+    del got_all
     sel = np.array([0, 1, 2047, 4094, 4095, 4096], np.int64)      # row 4096 starts at flat index 2^32
-    expect = orc.decompress_selected_rows(cols, sel, row_offs, bm, values)
-    got = out[torch.from_numpy(sel).cuda()].cpu().numpy().view(np.uint16)
-    assert np.array_equal(got, expect)
+    expect = full[sel].copy()
+    del full
     # and the row-subset entry point at the same offsets
     rsel = endor.decompress_rows(m, ro, torch.from_numpy(sel).cuda())
     torch.cuda.synchronize()

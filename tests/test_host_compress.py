@@ -105,21 +105,52 @@ def test_compress_u8_matches_oracle(shape, keep):
 
 
 @pytest.mark.parametrize("rows,cols,nblocks", [(2048, 4096, 8), (1031, 2053, 5), (96, 24, 3), (333, 64, 50), (5, 7, 3)])
-def test_row_blocks_are_self_contained_blobs(rows, cols, nblocks):
-    """A block of whole rows, cut where row*cols is a bitmap word boundary, is a valid
-    compressed matrix of its own: the oracle's Algorithm 2 on the block gives the block's rows."""
-    torch = pytest.importorskip("torch")
-    w = synth.pruned_fp16(rows, cols, 0.5, seed=50, row_skew=True)
+@pytest.mark.parametrize("wide", [True, False], ids=["fp16", "u8"])
+def test_row_blocks_are_self_contained_blobs(rows, cols, nblocks, wide):
+    """A block of whole rows, cut where row*cols is a bitmap word boundary (endor_row_block_cuts,
+    endor_row_block), is a valid compressed matrix of its own: the oracle's Algorithm 2 on the
+    block gives the block's rows."""
+    pytest.importorskip("torch")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=50, row_skew=True) if wide else synth.pruned_int8(rows, cols, 0.5, seed=50)
     c = endor.compress(w)
-    bm = torch.from_numpy(c.bitmap.copy())
-    vals = torch.from_numpy(c.values.view(np.int16).copy())
-    blobs = endor.row_blocks(c, (bm, vals), nblocks)
+    cuts = endor.row_block_cuts(rows, cols, nblocks)
+    assert cuts[0] == 0 and cuts[-1] == rows and all(a <= b for a, b in zip(cuts, cuts[1:]))
+    assert all((r * cols) % 64 == 0 for r in cuts[:-1])
+    blobs = endor.row_blocks(c, nblocks, pinned=False)
     assert sum(b.rows for b in blobs) == rows and sum(b.nnz for b in blobs) == c.nnz
     for b in blobs:
-        assert (b.row_begin * cols) % 64 == 0
-        sub = orc.decompress(b.rows, cols, b.bitmap.numpy()[: endor.bitmap_bytes(b.rows, cols)],
-                             b.values.numpy().view(np.uint16))
+        assert (b.row_begin * cols) % 64 == 0 and b.elem_bytes == c.values.dtype.itemsize
+        flat = b.keep.numpy()
+        nb = endor.bitmap_bytes(b.rows, cols)
+        assert b.values_ptr - b.bitmap_ptr == (nb + 255) // 256 * 256        # adjacent: one copy per blob
+        vals = flat[(nb + 255) // 256 * 256:].view(c.values.dtype)
+        assert vals.size == b.nnz
+        sub = orc.decompress(b.rows, cols, flat[:nb], vals)
         assert np.array_equal(sub, w[b.row_begin:b.row_begin + b.rows])
+        # and against the oracle's own row-block routine on the whole matrix
+        full = np.zeros((rows, cols), dtype=c.values.dtype)
+        k_end = orc._load().oracle_decompress_rows(c.values.dtype.itemsize, cols, b.row_begin, b.row_begin + b.rows,
+                                                   int(c.row_offsets[b.row_begin]), c.bitmap.ctypes.data,
+                                                   c.values.ctypes.data, full.ctypes.data)
+        assert k_end == int(c.row_offsets[b.row_begin + b.rows])
+        assert np.array_equal(full[b.row_begin:b.row_begin + b.rows], sub)
+
+
+def test_row_block_helpers_reject_bad_arguments():
+    import ctypes
+    L = endor.lib()
+    cuts = (ctypes.c_int64 * 4)()
+    assert L.endor_row_block_cuts(10, 64, 0, cuts) == 1
+    assert L.endor_row_block_cuts(-1, 64, 3, cuts) == 1
+    assert L.endor_row_block_cuts(10, 64, 3, None) == 1
+    assert L.endor_row_block_cuts(0, 64, 3, cuts) == 0 and list(cuts) == [0, 0, 0, 0]
+    ro = np.arange(11, dtype=np.int64) * 5
+    blob = (ctypes.c_byte * 64)()
+    fake = 0x1000
+    assert L.endor_row_block(10, 24, 2, fake, fake, ro.ctypes.data, 1, 5, fake, blob) == 1      # 24 bits: not a word boundary
+    assert L.endor_row_block(10, 24, 2, fake, fake, ro.ctypes.data, 8, 11, fake, blob) == 1     # past the matrix
+    assert L.endor_row_block(10, 24, 3, fake, fake, ro.ctypes.data, 0, 8, fake, blob) == 1      # element width
+    assert L.endor_row_block(10, 24, 2, fake, fake, ro.ctypes.data, 8, 10, fake, blob) == 0
 
 
 def _table_entries(ws: np.ndarray, n: int):

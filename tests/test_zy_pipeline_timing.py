@@ -1,0 +1,58 @@
+"""Timing property of the transfer pipeline (Section 4.1's order: the compressed weight is
+copied to the GPU and decompressed there; Section 6: overlap).  Kept in a file of its own,
+collected late, because it compares wall-clock times."""
+import time
+
+import numpy as np
+import pytest
+
+import paper_2406_11674_amd as endor
+from oracle import endor_oracle as orc
+from paper_2406_11674_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def test_h2d_pipeline_hides_decompression_under_the_copy():
+    """Copy everything, then decompress, against the two overlapped over row blocks on two copy
+    streams: the pipeline must take less time than the serial order (best of several runs each;
+    both are bound by the host link, whose copies repeat to a few microseconds)."""
+    rows, cols = 28672, 8192
+    c = endor.compress(synth.pruned_fp16(rows, cols, 0.5, seed=70))
+    whole = endor.pin(c)
+    blobs = endor.row_blocks(c, 8)
+    out = torch.empty((rows, cols), dtype=torch.int16, device="cuda")
+    outs = [out[b.row_begin:b.row_begin + b.rows] for b in blobs]
+    s_copy, s_copy2, s_comp = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    pipe = endor.Pipeline.for_blobs(blobs, s_copy, s_comp, copy_stream2=s_copy2)
+    stage = torch.empty(whole.keep.numel(), dtype=torch.uint8, device="cuda")
+    nb = endor.bitmap_bytes(rows, cols)
+    m = endor.DeviceMatrix(rows, cols, stage[:nb], stage[(nb + 255) // 256 * 256:].view(torch.int16), c.nnz)
+    ws = torch.empty(endor.workspace_bytes(rows, cols), dtype=torch.uint8, device="cuda")
+
+    def serial():
+        with torch.cuda.stream(s_copy):
+            stage.copy_(whole.keep, non_blocking=True)
+            endor.decompress(m, out=out, workspace=ws, stream=s_copy)
+
+    def best_of(fn, reps=9):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(reps):
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t)
+        return best
+
+    t_serial = best_of(serial)
+    out.fill_(0x7FFF)
+    t_pipe = best_of(lambda: pipe.run(blobs, outs))
+    print(f"copy then decompress {t_serial * 1e3:.3f} ms, pipeline over {len(blobs)} row blocks "
+          f"{t_pipe * 1e3:.3f} ms", flush=True)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, c.values))
+    assert t_pipe < t_serial
+    pipe.close()
