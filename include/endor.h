@@ -283,7 +283,7 @@ endor_status endor_compress_device_u8(int64_t rows, int64_t cols, const uint8_t 
  * columns of a down projection that belong to active neurons): d_out is rows x nsel,
  * d_out[i][q] = W[i][d_sel[q]].  One rank query per row and selected column, answered from
  * the bitmap and d_row_offsets.  Columns may repeat and come in any order; an index outside
- * [0, cols) leaves its output column untouched.  cols <= 2^19; rows*nsel < 2^34.
+ * [0, cols) leaves its output column untouched.  cols <= 2^18; rows*nsel < 2^34.
  * d_sel, d_row_offsets: device int64 arrays.  No workspace.
  */
 endor_status endor_decompress_cols(int64_t rows, int64_t cols,
