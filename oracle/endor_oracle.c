@@ -32,9 +32,9 @@
  *       point instruction ever touches a value.
  *
  * Algorithms 1 and 2 and the tables derived from them are integer / byte work, so
- * their results are exact.  The one floating-point routine, oracle_gemv_f16 at the
- * end of the file (the matrix-vector product on the decompressed matrix), converts
- * fp16 to double exactly and accumulates in double.
+ * their results are exact.  The floating-point routines at the end of the file
+ * (oracle_gemv_f16, oracle_gemm_f16_rows: the products of the decompressed matrix with
+ * one or a few vectors) convert fp16 to double exactly and accumulate in double.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -254,5 +254,31 @@ void oracle_gemv_f16(int64_t rows, int64_t cols, const uint8_t *bitmap, const ui
             acc += w * oracle_half_to_double(x[j]);
         }
         y[i] = acc;
+    }
+}
+
+/*
+ * The same product for a small batch of right-hand sides (the linear operation on a few
+ * tokens at once; Section 7's "Efficient Compute Unit" asks for computing on the sparse
+ * weight directly):
+ *     y[b][i] = sum_j W[i][j] * x[b][j]        b = 0 .. nb-1
+ * over the rows [row_begin, row_end) of W.  W is given DENSE, as the output of Algorithm 2
+ * (oracle_decompress); this routine is only the textbook triple loop on it, every fp16
+ * value converted exactly to double, sums in double, j ascending.
+ *
+ * dense   rows x cols fp16 patterns, row-major (the oracle's own decompressed matrix)
+ * x       nb x cols fp16 patterns, each right-hand side contiguous
+ * y       out, nb x rows doubles (y[b*rows + i]); only rows [row_begin,row_end) are written
+ */
+void oracle_gemm_f16_rows(int64_t rows, int64_t cols, int64_t row_begin, int64_t row_end,
+                          const uint16_t *dense, const uint16_t *x, int64_t nb, double *y)
+{
+    for (int64_t b = 0; b < nb; ++b) {
+        for (int64_t i = row_begin; i < row_end; ++i) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < cols; ++j)
+                acc += oracle_half_to_double(dense[i * cols + j]) * oracle_half_to_double(x[b * cols + j]);
+            y[b * rows + i] = acc;
+        }
     }
 }

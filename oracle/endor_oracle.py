@@ -62,6 +62,8 @@ def _load():
             lib.oracle_half_to_double_array.argtypes = [_p, _i64, _p]
             lib.oracle_gemv_f16.restype = None
             lib.oracle_gemv_f16.argtypes = [_i64, _i64, _p, _p, _p, _p]
+            lib.oracle_gemm_f16_rows.restype = None
+            lib.oracle_gemm_f16_rows.argtypes = [_i64, _i64, _i64, _i64, _p, _p, _i64, _p]
             _lib = lib
     return _lib
 
@@ -197,4 +199,30 @@ def gemv_f16(rows: int, cols: int, bitmap: np.ndarray, values: np.ndarray, x: np
         raise ValueError("values shorter than the number of 1 bits")
     y = np.empty(rows, dtype=np.float64)
     lib.oracle_gemv_f16(rows, cols, _ptr(bitmap), _ptr(values), _ptr(x), _ptr(y))
+    return y
+
+
+def gemm_f16(rows: int, cols: int, bitmap: np.ndarray, values: np.ndarray, X: np.ndarray,
+             threads: int = 1) -> np.ndarray:
+    """Y[b][i] = sum_j W[i][j] X[b][j] in double: W is first decompressed with Algorithm 2
+    (decompress above), then the C triple loop runs on the dense matrix.  X: (nb, cols) fp16
+    patterns.  `threads` > 1 only splits the rows into blocks, one OS thread each."""
+    lib = _load()
+    X = np.ascontiguousarray(X).view(np.uint16)
+    if X.ndim != 2 or X.shape[1] != cols:
+        raise ValueError("X must be (nb, cols)")
+    nb = X.shape[0]
+    dense = decompress(rows, cols, bitmap, np.ascontiguousarray(values, dtype=np.uint16))
+    y = np.empty((nb, rows), dtype=np.float64)
+    threads = max(1, min(threads, rows))
+    bounds = [rows * t // threads for t in range(threads + 1)]
+
+    def work(t):
+        lib.oracle_gemm_f16_rows(rows, cols, bounds[t], bounds[t + 1], _ptr(dense), _ptr(X), nb, _ptr(y))
+
+    if threads == 1:
+        work(0)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(work, range(threads)))
     return y

@@ -379,3 +379,57 @@ def test_gemv_nonfinite_x_propagates_like_the_dense_product():
     b, v, _ = orc.compress(W)
     y = orc.gemv_f16(2, 2, b, v, np.array([1.0, np.inf], np.float16))
     assert np.isnan(y[0]) and np.isnan(y[1])             # 0 * inf = nan, as with the dense matrix
+
+
+# ---------------------------------------------------------------------------
+# small-batch product (Section 7, "Efficient Compute Unit"): Y[b][i] = sum_j W[i][j] X[b][j]
+# ---------------------------------------------------------------------------
+def test_gemm_hand_built():
+    # W = [[1.5, 0, -2], [0, 0, 0.5]];  X = [[2, 100, 0.25], [0, 1, 4]]
+    #   b=0: [1.5*2 - 2*0.25, 0.5*0.25] = [2.5, 0.125];   b=1: [-2*4, 0.5*4] = [-8, 2]
+    W = np.array([[1.5, 0, -2.0], [0, 0, 0.5]], np.float16)
+    X = np.array([[2, 100, 0.25], [0, 1, 4]], np.float16)
+    b, v, _ = orc.compress(W)
+    Y = orc.gemm_f16(2, 3, b, v, X)
+    assert Y.shape == (2, 2) and Y.tolist() == [[2.5, 0.125], [-8.0, 2.0]]
+    # a transposed operand (X used as cols x nb) or swapped output axes would give other numbers
+    assert Y.tolist() != [[2.5, -8.0], [0.125, 2.0]]
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 5), (7, 13), (33, 65), (5, 4097), (40, 1000), (17, 300)], ids=str)
+@pytest.mark.parametrize("nb", [1, 3, 16])
+def test_gemm_equals_numpy_matmul_in_double(shape, nb):
+    rows, cols = shape
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=rows * 5 + cols)
+    X = np.random.default_rng(cols + nb).standard_normal((nb, cols)).astype(np.float16)
+    b, v, _ = orc.compress(w)
+    Y = orc.gemm_f16(rows, cols, b, v, X)
+    dense = w.view(np.float16).astype(np.float64)
+    ref = X.astype(np.float64) @ dense.T                    # (nb, rows), numpy's own order of addition
+    scale = np.abs(X.astype(np.float64)) @ np.abs(dense).T
+    assert np.all(np.abs(Y - ref) <= 1e-13 * scale + 1e-300)
+    # every right-hand side on its own is the single-vector routine, bit for bit
+    for k in range(nb):
+        assert np.array_equal(Y[k], orc.gemv_f16(rows, cols, b, v, X[k]))
+    # and the row-block split used for timing changes nothing
+    assert np.array_equal(Y, orc.gemm_f16(rows, cols, b, v, X, threads=3))
+
+
+def test_gemm_exact_on_small_integers():
+    """Integer-valued fp16 inputs: every product and partial sum is an integer below 2^53, so
+    the double result is the exact integer product, whatever the order of addition."""
+    rows, cols, nb = 9, 777, 5
+    g = np.random.default_rng(3)
+    wi = g.integers(-8, 9, (rows, cols)) * (g.random((rows, cols)) < 0.5)
+    xi = g.integers(-8, 9, (nb, cols))
+    b, v, _ = orc.compress(wi.astype(np.float16))
+    Y = orc.gemm_f16(rows, cols, b, v, xi.astype(np.float16))
+    assert np.array_equal(Y, (xi @ wi.T).astype(np.float64))
+
+
+def test_gemm_nonfinite_x_propagates_like_the_dense_product():
+    W = np.array([[1.0, 0.0], [0.0, 0.0]], np.float16)
+    b, v, _ = orc.compress(W)
+    Y = orc.gemm_f16(2, 2, b, v, np.array([[1.0, np.inf], [1.0, 2.0]], np.float16))
+    assert np.isnan(Y[0]).all()                           # 0 * inf = nan in both rows of W
+    assert Y[1].tolist() == [1.0, 0.0]                    # the finite right-hand side is untouched
