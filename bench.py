@@ -314,6 +314,16 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, keep):
     timed("gemv_f16", lambda: endor.gemv_f16(m, ro, x, y=y), n // 8 + 2 * nnz + 8 * (rows + 1) + 2 * cols + 4 * rows,
           note="endor_gemv_f16: bitmap + values + row offsets + x read, y written; a dense fp16 GEMV "
                "would read %d bytes" % (2 * n))
+    # small-batch product on the matrix cores: one expansion of W shared by nb right-hand sides
+    tab, _ = endor.build_offsets(m)
+    for nb in (1, 16):
+        X = torch.randn((nb, cols), device="cuda").to(torch.float16)
+        Y = torch.empty((nb, rows), dtype=torch.float32, device="cuda")
+        sc = torch.empty(max(256, endor.gemm_scratch_bytes(rows, cols, nb)), dtype=torch.uint8, device="cuda")
+        timed("gemm_f16_nb%d" % nb, lambda: endor.gemm_f16(m, tab, X, Y=Y, scratch=sc),
+              n // 8 + 2 * nnz + 2 * nb * cols + 4 * nb * rows,
+              note="endor_gemm_f16 with %d right-hand side(s): bitmap + values + X read, Y written; %.1f GFLOP per call"
+                   % (nb, 2e-9 * n * nb))
     # what the fused product replaces: decompress, then the library's dense fp16 matrix-vector product
     dense16 = endor.decompress(m).view(torch.float16)
     yd = torch.empty(rows, dtype=torch.float16, device="cuda")
@@ -324,6 +334,10 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, keep):
     timed("reference_decompress_then_mv",
           lambda: (endor.decompress(m, out=dbuf, workspace=ws1), torch.mv(dbuf.view(torch.float16), x, out=yd)),
           2 * n + n // 8 + 2 * nnz + 2 * n, note="endor_decompress followed by torch.mv: the unfused path")
+    X16 = torch.randn((16, cols), device="cuda").to(torch.float16)
+    Y16 = torch.empty((16, rows), dtype=torch.float16, device="cuda")
+    timed("reference_dense_mm_nb16", lambda: torch.matmul(X16, dense16.t(), out=Y16), 2 * n + 2 * 16 * cols + 2 * 16 * rows,
+          note="torch.matmul of 16 right-hand sides with the already decompressed fp16 matrix (the vendor GEMM)")
     return out
 
 

@@ -312,6 +312,30 @@ endor_status endor_gemv_f16(int64_t rows, int64_t cols,
                             const uint16_t *d_x, float *d_y, void *stream);
 
 /*
+ * DEVICE.  Fused consumer for a small batch: Y = X W^T for nb <= ENDOR_GEMM_MAX_BATCH
+ * right-hand sides, straight from the compressed form, on the matrix cores (Section 7,
+ * "Efficient Compute Unit": compute on the sparse weight; Section 3.1: the linear operation
+ * itself).  The expansion of W is done once and shared by all right-hand sides.
+ *   d_x      nb vectors of cols fp16 values; vector b starts at d_x + b*ldx (ldx >= cols)
+ *   d_y      out, nb x rows fp32: d_y[b*rows + i] = sum_j W[i][j] * x_b[j]; fp16 products are
+ *            exact, sums are fp32 (32 products per matrix instruction); elements whose bit is
+ *            0 enter as +0.0, fp16 subnormals count in full
+ *   d_workspace   the tile offset table of this bitmap (endor_build_offsets or any
+ *            endor_decompress* call wrote it): it gives every wave its starting point
+ *   d_scratch     endor_gemm_scratch_bytes(rows, cols, nb) bytes (256-byte aligned; may be NULL
+ *            when that is 0): partial sums of the column ranges the work is split into; they
+ *            are added in a fixed order, so results are reproducible from run to run
+ * A 16-byte aligned d_x with ldx a multiple of 8 selects the fast load path.  rows < 2^31.
+ */
+#define ENDOR_GEMM_MAX_BATCH 16
+size_t endor_gemm_scratch_bytes(int64_t rows, int64_t cols, int nb);
+endor_status endor_gemm_f16(int64_t rows, int64_t cols,
+                            const uint8_t *d_bitmap, const uint16_t *d_values, int64_t nnz,
+                            const void *d_workspace, size_t workspace_bytes,
+                            const uint16_t *d_x, int64_t ldx, int nb, float *d_y,
+                            void *d_scratch, size_t scratch_bytes, void *stream);
+
+/*
  * DEVICE.  Check mode (the end condition of Algorithm 2: its counter k must equal the
  * number of packed values).  For each matrix of the batch, compare its nnz with the
  * number of 1 bits of its bitmap as recorded in the offset tables that

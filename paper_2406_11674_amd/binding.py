@@ -18,7 +18,7 @@ __all__ = [
     "bitmap_bytes", "workspace_bytes", "batch_workspace_bytes", "compress", "to_device",
     "build_offsets", "build_offsets_host", "decompress", "decompress_with_offsets",
     "decompress_batch", "decompress_batch_static", "build_offsets_batch", "decompress_batch_with_offsets",
-    "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "HostBlob", "pin", "row_blocks", "row_block_cuts", "stage_bytes", "Pipeline", "PIPELINE_SLOTS", "check_batch",
+    "decompress_rows", "decompress_cols", "compress_device", "gemv_f16", "gemm_f16", "gemm_scratch_bytes", "HostBlob", "pin", "row_blocks", "row_block_cuts", "stage_bytes", "Pipeline", "PIPELINE_SLOTS", "check_batch",
 ]
 
 TILE_ELEMS = 4096
@@ -98,6 +98,10 @@ def lib() -> ctypes.CDLL:
         L.endor_decompress_batch_static.argtypes = [_p, ctypes.c_int, _p]
         L.endor_gemv_f16.restype = ctypes.c_int
         L.endor_gemv_f16.argtypes = [_i64, _i64, _p, _p, _i64, _p, _p, _p, _p]
+        L.endor_gemm_scratch_bytes.restype = _sz
+        L.endor_gemm_scratch_bytes.argtypes = [_i64, _i64, ctypes.c_int]
+        L.endor_gemm_f16.restype = ctypes.c_int
+        L.endor_gemm_f16.argtypes = [_i64, _i64, _p, _p, _i64, _p, _sz, _p, _i64, ctypes.c_int, _p, _p, _sz, _p]
         L.endor_stage_bytes.restype = _sz
         L.endor_stage_bytes.argtypes = [_i64, _i64, _i64, ctypes.c_int]
         L.endor_row_block_cuts.restype = ctypes.c_int
@@ -414,6 +418,32 @@ def gemv_f16(m: DeviceMatrix, row_offsets, x, y=None, stream=None):
     _check(lib().endor_gemv_f16(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(row_offsets),
                                 _dptr(x), _dptr(y), _stream_handle(stream)), "endor_gemv_f16")
     return y
+
+
+def gemm_scratch_bytes(rows: int, cols: int, nb: int) -> int:
+    return int(lib().endor_gemm_scratch_bytes(rows, cols, nb))
+
+
+def gemm_f16(m: DeviceMatrix, workspace, X, Y=None, scratch=None, stream=None):
+    """endor_gemm_f16: Y (fp32, nb x rows) = X W^T with W in compressed form; X: (nb, cols) fp16
+    device tensor (row stride = ldx), workspace: the matrix's tile offset table."""
+    torch = _torch()
+    if m.elem_bytes != 2 or X.element_size() != 2 or X.dim() != 2 or X.shape[1] != m.cols or X.stride(1) != 1:
+        raise ValueError("gemm_f16 needs 16-bit values and an fp16 X of shape (nb, cols)")
+    nb = int(X.shape[0])
+    if Y is None:
+        Y = torch.empty((nb, m.rows), dtype=torch.float32, device=m.bitmap.device)
+    if Y.dtype != torch.float32 or Y.numel() != nb * m.rows or not Y.is_contiguous():
+        raise ValueError("Y must be a contiguous fp32 tensor of nb*rows elements")
+    need = gemm_scratch_bytes(m.rows, m.cols, nb) if nb and m.rows and m.cols else 0
+    if scratch is None and need:
+        scratch = torch.empty(need, dtype=torch.uint8, device=m.bitmap.device)
+    _check(lib().endor_gemm_f16(m.rows, m.cols, _dptr(m.bitmap), _dptr(m.values), m.nnz, _dptr(workspace),
+                                0 if workspace is None else workspace.numel(), _dptr(X),
+                                int(X.stride(0)) if nb > 1 else max(m.cols, int(X.stride(0))), nb, _dptr(Y),
+                                _dptr(scratch), 0 if scratch is None else scratch.numel(), _stream_handle(stream)),
+           "endor_gemm_f16")
+    return Y
 
 
 # ------------------------------------------------------------------ host -> device pipeline

@@ -12,6 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libendor.so")
 SOURCES = [os.path.join(HERE, "csrc", "endor_kernels.hip"),
+           os.path.join(HERE, "csrc", "endor_gemm.hip"),
            os.path.join(HERE, "csrc", "endor_pipeline.hip"),
            os.path.join(HERE, "csrc", "endor_host.cpp")]
 # the streaming yardstick kernels bench.py times beside the library (not part of the product path)

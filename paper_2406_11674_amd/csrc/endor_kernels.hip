@@ -38,9 +38,17 @@
 #include <mutex>
 
 #include "endor.h"
+#include "endor_device.h"
 #include "endor_layout.h"
 
 namespace {
+
+using endor_device::chunk_base;
+using endor_device::dpp_or_zero;
+using endor_device::row_inclusive_scan;
+using endor_device::u32x4;
+using endor_device::wave_inclusive_scan;
+using endor_device::wave_sum;
 
 using endor_layout::kTileElems;      // flat positions per tile
 using endor_layout::kTileWords;      // 64-bit bitmap words per tile (= lanes per wave)
@@ -67,8 +75,6 @@ static_assert(kTilesPerChunk == 256 && kCountBlock >= kTilesPerChunk && kCountTi
                   kCountSteps >= 1,
               "the tile-offset workgroup scans one tile count per thread");
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 struct MatParams {
     const uint64_t *bitmap;
     const void *values;     // nnz elements of 1 or 2 bytes
@@ -86,35 +92,6 @@ struct BatchParams {
     int count;
 };
 
-// ---------------------------------------------------------------- wave primitives
-
-template <int kCtrl, int kRowMask>
-__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t x) {
-    // lanes without a source, and rows masked off, receive 0
-    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, kRowMask, 0xf, true));
-}
-
-// inclusive prefix sum within each row of 16 lanes (row_shr:1,2,4,8)
-__device__ __forceinline__ uint32_t row_inclusive_scan(uint32_t x) {
-    x += dpp_or_zero<0x111, 0xf>(x);
-    x += dpp_or_zero<0x112, 0xf>(x);
-    x += dpp_or_zero<0x114, 0xf>(x);
-    x += dpp_or_zero<0x118, 0xf>(x);
-    return x;
-}
-
-// inclusive prefix sum over the 64 lanes of a wave
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
-    x = row_inclusive_scan(x);
-    x += dpp_or_zero<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
-    x += dpp_or_zero<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
-    return x;
-}
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
-    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(wave_inclusive_scan(x)), 63));
-}
-
 // Bitmap word `w` of a matrix with `full_words` complete words and `tail_bits`
 // valid bits in the word after them; pad bits and words past the end read as 0.
 __device__ __forceinline__ uint64_t load_word_guarded(const uint64_t *bitmap, int64_t w,
@@ -128,18 +105,6 @@ __device__ __forceinline__ int find_matrix(const BatchParams &P, uint32_t chunk)
     int mi = 0;
     for (int i = 1; i < P.count; ++i) mi = (chunk >= P.m[i].chunk_begin) ? i : mi;
     return mi;
-}
-
-// Number of 1 bits before chunk c of the matrix: sum of the earlier chunks' totals.
-// c < 2^14 and a total is at most 2^20, so a lane's partial sum fits 32 bits; the
-// two 16-bit halves are summed across lanes separately to keep 64 bits.
-__device__ __forceinline__ uint64_t chunk_base(const uint32_t *chunk_total, uint32_t c, uint32_t lane) {
-    if (c == 0) return 0;
-    uint32_t part = 0;
-    for (uint32_t j = lane; j < c; j += 64) part += chunk_total[j];
-    const uint32_t lo = wave_sum(part & 0xffffu);
-    const uint32_t hi = wave_sum(part >> 16);
-    return uint64_t(lo) + (uint64_t(hi) << 16);
 }
 
 // ---------------------------------------------------------------- kernel 1: tile offsets

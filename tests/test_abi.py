@@ -116,6 +116,17 @@ def test_widened_entry_points_reject_bad_arguments_without_launching():
     assert L.endor_gemv_f16(4, 64, fake, fake, 10, fake, fake, None, None) == 1
     assert L.endor_gemv_f16(4, 64, fake, fake, 10, fake, fake, fake + 2, None) == 1
     assert L.endor_gemv_f16(0, 64, None, None, 0, None, None, None, None) == 0
+    # small-batch product
+    assert L.endor_gemm_f16(4, 64, None, fake, 10, fake, ws, fake, 64, 2, fake, None, 0, None) == 1
+    assert L.endor_gemm_f16(4, 64, fake, fake, 10, None, ws, fake, 64, 2, fake, None, 0, None) == 1
+    assert L.endor_gemm_f16(4, 64, fake, fake, 10, fake, 16, fake, 64, 2, fake, None, 0, None) == 2
+    assert L.endor_gemm_f16(4, 64, fake, fake, 10, fake, ws, fake, 63, 2, fake, None, 0, None) == 1     # ldx < cols
+    assert L.endor_gemm_f16(4, 64, fake, fake, 10, fake, ws, fake, 64, 17, fake, None, 0, None) == 1    # batch too large
+    assert L.endor_gemm_f16(4, 64, fake, fake, 10, fake, ws, fake, 64, 2, None, None, 0, None) == 1
+    assert L.endor_gemm_f16(64, 4096, fake, fake, 10, fake, ws, fake, 4096, 2, fake, None, 0, None) == 1  # scratch missing
+    assert L.endor_gemm_f16(0, 64, None, None, 0, None, 0, None, 64, 2, None, None, 0, None) == 0
+    assert endor.gemm_scratch_bytes(4, 64, 2) == 0 and endor.gemm_scratch_bytes(64, 4096, 2) > 0
+    assert endor.gemm_scratch_bytes(64, 4096, 17) == 0
     # device compressor
     assert L.endor_compress_device(4, 64, None, fake, fake, 256, fake, ws, None, fake, None) == 1
     assert L.endor_compress_device(4, 64, fake, None, fake, 256, fake, ws, None, fake, None) == 1

@@ -642,6 +642,135 @@ def test_gemv_full_size(shape):
 
 
 # ---------------------------------------------------------------------------
+# fused small-batch product on the matrix cores: Y = X W^T, nb <= 16
+# ---------------------------------------------------------------------------
+def _gemm_tolerance(w_bits, X16, cols):
+    """fp16 products are exact in fp32.  A matrix instruction adds 32 of them to the fp32
+    accumulator; its internal order is not documented, so each instruction is charged two
+    roundings of the running magnitude (a probe on the device returned the correctly rounded
+    exact sum, i.e. one), and the column ranges are added with one rounding each:
+    |err| <= (2 * ceil(cols/32) + 16 + 8) * 2^-24 * sum_j |W_ij x_bj|, plus underflow."""
+    absw = np.abs(w_bits.view(np.float16).astype(np.float64))
+    absx = np.abs(X16.astype(np.float64))
+    return (2 * ((cols + 31) // 32) + 24) * 2.0 ** -24 * 1.01 * (absx @ absw.T) + 2.0 ** -126
+
+
+def _gpu_gemm(c, X16, **kw):
+    m = endor.to_device(c)
+    ws, _ = endor.build_offsets(m)
+    Y = endor.gemm_f16(m, ws, torch.from_numpy(X16.view(np.int16)).cuda().view(torch.float16), **kw)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy().astype(np.float64)
+
+
+GEMM_SHAPES = [(1, 1), (3, 5), (7, 13), (16, 256), (17, 257), (33, 65), (5, 4095), (5, 4096), (5, 4097), (40, 1000),
+               (64, 8192), (16, 28672), (9, 12345), (100, 2053), (300, 4099)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES, ids=str)
+@pytest.mark.parametrize("nb", [1, 3, 16])
+def test_gemm_matches_oracle(shape, nb):
+    rows, cols = shape
+    _say(f"gemm case shape={shape} nb={nb}")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=rows * 5 + cols, row_skew=True)
+    w.reshape(-1)[:: 97] = 0x0001                      # fp16 subnormals among the values
+    X16 = np.random.default_rng(cols + nb).standard_normal((nb, cols)).astype(np.float16)
+    c = endor.compress(w)
+    got = _gpu_gemm(c, X16)
+    ref = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= _gemm_tolerance(w, X16, cols))
+
+
+@pytest.mark.parametrize("shape", [(33, 65), (100, 2053), (64, 8192), (300, 4099)], ids=str)
+def test_gemm_is_exact_on_integer_valued_inputs(shape):
+    """Small integers in W and X: every product and every partial sum is an integer below 2^24,
+    exactly representable in fp32, so the result must equal the oracle's bit for bit whatever
+    the order of addition - a dropped, doubled or misplaced term cannot hide in a tolerance."""
+    rows, cols = shape
+    g = np.random.default_rng(rows + cols)
+    wi = (g.integers(-8, 9, (rows, cols)) * (g.random((rows, cols)) < 0.5)).astype(np.float16)
+    X16 = g.integers(-8, 9, (16, cols)).astype(np.float16)
+    c = endor.compress(wi)
+    got = _gpu_gemm(c, X16)
+    assert np.array_equal(got, orc.gemm_f16(rows, cols, c.bitmap, c.values, X16))
+
+
+def test_gemm_subnormal_inputs_count_in_full():
+    rows, cols = 20, 700
+    g = np.random.default_rng(5)
+    wi = (g.integers(1, 1024, (rows, cols)) * (g.random((rows, cols)) < 0.5)).astype(np.uint16)   # fp16 subnormals
+    X16 = g.integers(-4, 5, (4, cols)).astype(np.float16)
+    c = endor.compress(wi)
+    got = _gpu_gemm(c, X16)
+    ref = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+    assert np.any(ref != 0) and np.array_equal(got, ref)          # integers * 2^-24: exact in fp32
+
+
+def test_gemm_unaligned_x_and_padded_rows_of_x():
+    rows, cols, nb = 40, 1000, 5
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=8)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    ws, _ = endor.build_offsets(m)
+    X16 = np.random.default_rng(1).standard_normal((nb, cols)).astype(np.float16)
+    ref = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+    tol = _gemm_tolerance(w, X16, cols)
+    # rows of X 1003 elements apart, starting 2 bytes off a 16-byte boundary: the slow load path
+    buf = torch.zeros(nb * 1003 + 9, dtype=torch.float16, device="cuda")
+    Xd = torch.as_strided(buf, (nb, cols), (1003, 1), storage_offset=1)
+    Xd.copy_(torch.from_numpy(X16.view(np.int16)).cuda().view(torch.float16))
+    Y = endor.gemm_f16(m, ws, Xd)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(Y.cpu().numpy().astype(np.float64) - ref) <= tol)
+    # aligned, rows 1008 apart: the fast path with ldx > cols
+    buf2 = torch.zeros(nb * 1008, dtype=torch.float16, device="cuda")
+    Xe = torch.as_strided(buf2, (nb, cols), (1008, 1))
+    Xe.copy_(Xd)
+    Y2 = endor.gemm_f16(m, ws, Xe)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(Y2.cpu().numpy().astype(np.float64) - ref) <= tol)
+
+
+def test_gemm_nonfinite_x_like_the_dense_product():
+    rows, cols = 4, 100
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=9)
+    w[0, 7] = 0            # a zero element meets x = inf: 0 * inf = nan, as with the dense matrix
+    w[1, 7] = 0x3C00
+    X16 = np.random.default_rng(2).standard_normal((3, cols)).astype(np.float16)
+    X16[1, 7] = np.inf
+    c = endor.compress(w)
+    got = _gpu_gemm(c, X16)
+    ref = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isinf(got), np.isinf(ref))
+    ok = np.isfinite(ref)
+    assert np.all(np.abs(got - ref)[ok] <= _gemm_tolerance(w, X16, cols)[ok])
+
+
+@pytest.mark.parametrize("shape", [(8192, 28672), (28672, 8192)], ids=["down_proj", "gate_proj"])
+def test_gemm_full_size(shape):
+    """Both orientations of the Llama2-70B FFN at full size, 16 right-hand sides, every output:
+    random fp16 data within the derived bound, and integer-valued data exactly."""
+    rows, cols = shape
+    _say(f"gemm full size {shape}")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=synth.seed_for(3, 6 if rows == 8192 else 4))
+    X16 = np.random.default_rng(11).standard_normal((16, cols)).astype(np.float16)
+    c = endor.compress(w)
+    got = _gpu_gemm(c, X16)
+    ref = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16, threads=16)
+    tol = np.concatenate([_gemm_tolerance(w[r0:r0 + 1024], X16, cols) for r0 in range(0, rows, 1024)], axis=1)
+    assert np.all(np.abs(got - ref) <= tol)
+    # the same bitmap with small integers as values, and integer right-hand sides: exact
+    g = np.random.default_rng(12)
+    vi = g.integers(1, 9, c.nnz).astype(np.float16).view(np.uint16)
+    vi[g.random(c.nnz) < 0.5] |= 0x8000                                   # signs
+    Xi = g.integers(-8, 9, (16, cols)).astype(np.float16)
+    ci = endor.Compressed(rows, cols, c.bitmap, vi, c.row_offsets)
+    got = _gpu_gemm(ci, Xi)
+    assert np.array_equal(got, orc.gemm_f16(rows, cols, c.bitmap, vi, Xi, threads=16))
+
+
+# ---------------------------------------------------------------------------
 # precondition violations stay memory-safe; check mode reports them
 # ---------------------------------------------------------------------------
 def test_short_values_are_zero_extended_and_nothing_past_nnz_is_read():
