@@ -263,6 +263,9 @@ def extras_leg(endor, synth, torch, np, host, shapes, cfg, keep):
     ws8 = torch.empty(max(256, endor.workspace_bytes(rows, cols)), dtype=torch.uint8, device="cuda")
     timed("decompress_u8", lambda: endor.decompress(m8, out=o8, workspace=ws8), n + n // 8 + c8.nnz,
           note="endor_decompress_u8: offsets + expand, 1 + 1/8 + p bytes per element")
+    endor.build_offsets(m8, workspace=ws8)
+    timed("decompress_u8_with_offsets", lambda: endor.decompress_with_offsets(m8, ws8, out=o8), n + n // 8 + c8.nnz,
+          note="endor_decompress_u8_with_offsets: the expand kernel alone (table built once or shipped with the blob)")
     del w8, c8, m8, o8
 
     # row subset: a tenth of the rows, sorted
@@ -439,6 +442,7 @@ def main() -> int:
                          "decompression on a second stream")
     ap.add_argument("--overlap-blocks", type=int, default=4, help="row blocks per matrix in the pipeline")
     ap.add_argument("--extras", action="store_true", help="with --only: also time the widened entry points")
+    ap.add_argument("--ceilings", action="store_true", help="with --only: also run the streaming yardstick kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (a reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -569,7 +573,7 @@ def main() -> int:
         del c8, o8
         torch.cuda.empty_cache()
         result["configs"] = configs
-    if full and not args.no_ceilings:
+    if (full and not args.no_ceilings) or (args.only and args.ceilings):
         result["ceilings"] = ceilings_leg(torch)
 
     print(json.dumps(result), flush=True)

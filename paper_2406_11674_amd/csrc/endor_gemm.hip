@@ -17,10 +17,12 @@
 //   1. load the lane's 64 bitmap bits of the segment; popcount; prefix over the row's four
 //      words (DPP quad broadcasts).  Each row has its own cursor into `values` (its 1 bits
 //      so far), so the 16 rows are 16 independent streams.
-//   2. load the row's value slice for the segment: 16-byte units from the 16-byte boundary
-//      below the cursor, unit q*4 + j in round q (four lanes cover 64 contiguous bytes of a
-//      row per round, nine rounds cover the worst case of 256 values), guarded so that
-//      nothing outside values[0, nnz) is read; store them to the row's staging area in LDS.
+//   2. load the rows' value slices for the segment: 16-byte units from the 16-byte boundary
+//      below each cursor.  For this the lanes regroup as eight per row (rows l/8 and 8 + l/8),
+//      so that a load instruction fetches whole 128-byte lines (with four lanes per row and
+//      64-byte pieces the counters showed 1.4 times the bytes fetched); five rounds cover the
+//      worst case of 256 values.  Guarded so that nothing outside values[0, nnz) is read.  The
+//      units go to the rows' staging areas in LDS.
 //   3. per bitmap byte, one table entry: (offset of the byte's first value in the staging
 //      area) << 8 | the byte.
 //   4. eight steps: read the entry of (row, byte), look the byte up in a table built once
@@ -63,8 +65,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kRows = 16;               // rows of W per wave: the M of the matrix instruction
 constexpr int kSegCols = 256;           // columns per round
 constexpr int kSteps = kSegCols / 32;   // matrix instructions per round
-constexpr int kRounds = 9;              // 16-byte units a lane loads per round of values: 4 lanes x 9 >= 33
-constexpr int kRowUnits = 4 * kRounds;  // staging units per row
+constexpr int kRounds = 5;              // rounds of value loads per half of the rows: 8 lanes x 5 units >= 33
+constexpr int kRowUnits = 8 * kRounds;  // staging units per row
 constexpr int kInfoStride = 36;         // dwords per row of the entry table (32 used; 36 spreads the LDS banks)
 constexpr int kMaxSplit = 16;           // column ranges per row group at most
 
@@ -133,8 +135,9 @@ __device__ __forceinline__ uint64_t bits_at(const uint64_t *bitmap, int64_t nwor
 // what a lane has in flight for the coming round
 struct Round {
     uint64_t word;      // the lane's 64 bitmap bits (row l/4, word l%4 of the segment)
-    u32x4 v[kRounds];   // its units of the row's value slice
-    uint32_t nunits;    // units the row's slice spans
+    u32x4 va[kRounds];  // units of the value slice of row l/8 ...
+    u32x4 vb[kRounds];  // ... and of row 8 + l/8 (value-loading role: unit q*8 + l%8 in round q)
+    uint32_t na, nb;    // units those two rows' slices span
     uint32_t first2;    // 2 * (staging index of the first value of the lane's word)
     u32x4 xb[kSteps];   // fragments of X (as multiplying lane: right-hand side l%16, column block l/16)
 };
@@ -261,21 +264,38 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
         const uint32_t cnt = p0 + p1 + p2 + p3;  // <= 256
         const uintptr_t a16 = cursor & ~uintptr_t(15);
         const uint32_t shift = static_cast<uint32_t>(cursor - a16) >> 1;  // values of slack in front
-        R.nunits = cnt ? ((shift + cnt) * 2 + 15) >> 4 : 0;              // <= 33
+        const uint32_t nunits = cnt ? ((shift + cnt) * 2 + 15) >> 4 : 0;  // <= 33
         R.first2 = 2 * (shift + before);
         // a row slice that lies inside values[0, nnz) with its rounding to 16-byte units (all but
         // the first and last few values of the array) needs no per-unit range checks
-        const bool inside = a16 >= vbeg && a16 + 16 * uintptr_t(R.nunits) <= vend;
-        if (__builtin_amdgcn_ballot_w64(!inside) == 0) {  // wave-uniform
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(a16) + lj;
+        const bool inside = a16 >= vbeg && a16 + 16 * uintptr_t(nunits) <= vend;
+        const bool all_inside = __builtin_amdgcn_ballot_w64(!inside) == 0;  // wave-uniform
+        // Value-loading role: eight lanes per row, so that one load instruction fetches whole
+        // 128-byte lines (rows l/8 and 8 + l/8; their slice start and length come from the
+        // lanes that own the rows' cursors).
+        const uint32_t a_lo = static_cast<uint32_t>(a16), a_hi = static_cast<uint32_t>(a16 >> 32);
+        const int own_a = static_cast<int>(16 * (lane >> 3)), own_b = own_a + 128;  // byte index of lane 4*row
+        const uintptr_t base_a = (uintptr_t(static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, a_hi))) << 32) |
+                                 static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, a_lo));
+        const uintptr_t base_b = (uintptr_t(static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, a_hi))) << 32) |
+                                 static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, a_lo));
+        R.na = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, static_cast<int>(nunits)));
+        R.nb = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, static_cast<int>(nunits)));
+        const uint32_t sub = lane & 7;
+        if (all_inside) {
+            const u32x4 *pa = reinterpret_cast<const u32x4 *>(base_a) + sub;
+            const u32x4 *pb = reinterpret_cast<const u32x4 *>(base_b) + sub;
 #pragma unroll
-            for (int q = 0; q < kRounds; ++q)
-                if (uint32_t(q * 4) + lj < R.nunits) R.v[q] = __builtin_nontemporal_load(src + q * 4);
+            for (int q = 0; q < kRounds; ++q) {
+                if (uint32_t(q * 8) + sub < R.na) R.va[q] = __builtin_nontemporal_load(pa + q * 8);
+                if (uint32_t(q * 8) + sub < R.nb) R.vb[q] = __builtin_nontemporal_load(pb + q * 8);
+            }
         } else {
 #pragma unroll
             for (int q = 0; q < kRounds; ++q) {
-                const uint32_t u = q * 4 + lj;
-                if (u < R.nunits) R.v[q] = load_values16(a16 + 16 * uintptr_t(u), vbeg, vend);
+                const uint32_t u = q * 8 + sub;
+                if (u < R.na) R.va[q] = load_values16(base_a + 16 * uintptr_t(u), vbeg, vend);
+                if (u < R.nb) R.vb[q] = load_values16(base_b + 16 * uintptr_t(u), vbeg, vend);
             }
         }
         cursor += 2 * uintptr_t(cnt);
@@ -330,12 +350,17 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
             u32x4 *ip = reinterpret_cast<u32x4 *>(&S.info[lr][lj * 8]);
             ip[0] = lo;
             ip[1] = hi;
+            const uint32_t ra = lane >> 3, sub = lane & 7;
 #pragma unroll
             for (int q = 0; q < kRounds; ++q) {
-                const uint32_t u = q * 4 + lj;
-                if (u < R.nunits) {
-                    S.stage[lr][2 * u] = uint64_t(R.v[q].x) | (uint64_t(R.v[q].y) << 32);
-                    S.stage[lr][2 * u + 1] = uint64_t(R.v[q].z) | (uint64_t(R.v[q].w) << 32);
+                const uint32_t u = q * 8 + sub;
+                if (u < R.na) {
+                    S.stage[ra][2 * u] = uint64_t(R.va[q].x) | (uint64_t(R.va[q].y) << 32);
+                    S.stage[ra][2 * u + 1] = uint64_t(R.va[q].z) | (uint64_t(R.va[q].w) << 32);
+                }
+                if (u < R.nb) {
+                    S.stage[ra + 8][2 * u] = uint64_t(R.vb[q].x) | (uint64_t(R.vb[q].y) << 32);
+                    S.stage[ra + 8][2 * u + 1] = uint64_t(R.vb[q].z) | (uint64_t(R.vb[q].w) << 32);
                 }
             }
         }
