@@ -190,18 +190,26 @@ struct Shape {
     static constexpr int kLaneElems = 16 / E;                  // 8 or 16
     static constexpr int kSteps = kTileElems / (64 * kLaneElems);  // 8 or 4
     static constexpr int kLanesPerWord = 64 / kLaneElems;      // 8 or 4
-    // LDS staging of the tile's value slice in 16-byte units: up to kLaneElems-1 elements
-    // of alignment slack in front, 4096 values, and kLaneElems-1 elements a lane may
-    // read past its last value (those reads are masked off by the bits)
-    static constexpr int kStageChunks = (E * (2 * (kLaneElems - 1) + kTileElems) + 15) / 16;
-    static constexpr int kStageRounds = (kStageChunks + 63) / 64;
 };
 
-template <int E>
+// LDS a wave needs to expand a tile.  kCap = values the staging area holds at once: 4096 (a
+// whole tile, whatever its density) or, for matrices known to be sparse, 1024 - a tile with more
+// 1 bits than that is then expanded step by step (slower, but such tiles are rare there) and
+// the smaller footprint lets more waves share a compute unit, which is what a store-dominated
+// matrix wants (measured at one element in ten kept: 103 -> 97 us on 8192 x 28672).
+template <int E, int kCap = kTileElems>
 struct alignas(16) WaveScratch {
-    u32x4 stage[Shape<E>::kStageChunks];  // the tile's slice of `values`, from the 16-byte boundary below it
-    uint64_t words[kTileWords];           // the tile's bitmap words
-    uint32_t start[kTileWords];           // per word: index into `stage` (in elements) of its first value
+    static_assert(kCap >= 1024 && kCap <= kTileElems, "a step covers up to 1024 values");
+    static constexpr int kLaneElems = Shape<E>::kLaneElems;
+    // staging in 16-byte units: up to kLaneElems-1 elements of alignment slack in front, kCap
+    // values, and kLaneElems-1 elements a lane may read past its last value (those reads are
+    // masked off by the bits)
+    static constexpr int kStageChunks = (E * (2 * (kLaneElems - 1) + kCap) + 15) / 16;
+    static constexpr int kStageRounds = (kStageChunks + 63) / 64;
+    static constexpr uint32_t kMaxIndex = kStageChunks * (16 / E) - kLaneElems;  // last index a gather may start at
+    u32x4 stage[kStageChunks];   // the tile's slice of `values`, from the 16-byte boundary below it
+    uint64_t words[kTileWords];  // the tile's bitmap words
+    uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
 };
 
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
@@ -277,6 +285,52 @@ struct StoreSink {
     }
 };
 
+// One step of the expansion: every lane turns kLaneElems bitmap bits into 16 bytes of output.
+// S.words and S.start (per word: index into S.stage of its first value) are in place.
+template <int E, int kCap, class Sink>
+__device__ __forceinline__ void expand_step(const WaveScratch<E, kCap> &S, int k, uint32_t lane, Sink &sink) {
+    using Sh = Shape<E>;
+    const uint32_t wi = k * Sh::kLaneElems + lane / Sh::kLanesPerWord;
+    const uint64_t w = S.words[wi];
+    const uint32_t sh = (lane % Sh::kLanesPerWord) * Sh::kLaneElems;
+    const uint32_t bits = static_cast<uint32_t>(w >> sh) & ((1u << Sh::kLaneElems) - 1);
+    uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
+    // with a whole tile staged the index cannot leave the staging area; with a smaller area a
+    // table that does not belong to the bitmap could make it, so it is clamped
+    if (kCap < kTileElems) s = s > WaveScratch<E, kCap>::kMaxIndex ? WaveScratch<E, kCap>::kMaxIndex : s;
+    // every element is read from the staging area at its rank; the ones whose bit is 0
+    // pick up a neighbour's value and are masked to the all-zero pattern.
+    u32x4 d;
+    if (E == 2) {
+        const uint16_t *sp = reinterpret_cast<const uint16_t *>(S.stage) + s;
+        uint32_t h[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
+        d.x = (h[0] | (h[1] << 16)) & half_mask(bits);
+        d.y = (h[2] | (h[3] << 16)) & half_mask(bits >> 2);
+        d.z = (h[4] | (h[5] << 16)) & half_mask(bits >> 4);
+        d.w = (h[6] | (h[7] << 16)) & half_mask(bits >> 6);
+    } else {
+        const uint8_t *sp = reinterpret_cast<const uint8_t *>(S.stage) + s;
+        uint32_t h[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
+        d.x = (h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24)) & byte_mask(bits);
+        d.y = (h[4] | (h[5] << 8) | (h[6] << 16) | (h[7] << 24)) & byte_mask(bits >> 4);
+        d.z = (h[8] | (h[9] << 8) | (h[10] << 16) | (h[11] << 24)) & byte_mask(bits >> 8);
+        d.w = (h[12] | (h[13] << 8) | (h[14] << 16) | (h[15] << 24)) & byte_mask(bits >> 12);
+    }
+    sink(k, (k * 64 + lane) * Sh::kLaneElems, d);
+}
+
+// LDS operations of one wave execute in issue order, so reads after this point see the writes
+// before it; the fences only keep the compiler from moving them.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Expand one tile with one wave.
 //   word     this lane's 64 bitmap bits of the tile (bits past the end already cleared)
 //   vaddr    byte address of the tile's first value; cnt = number of 1 bits in the tile
@@ -284,76 +338,69 @@ struct StoreSink {
 //   sink     receives, per step k, the 16 expanded bytes of this lane: sink(k, le, d) with le
 //            the index inside the tile of the lane's first element
 // The caller has not touched S since the wave's previous call returned.
-template <int E, class Sink>
-__device__ __forceinline__ void expand_tile(WaveScratch<E> &S, uint32_t lane, uint64_t word, uintptr_t vaddr,
+// (Measured alternatives to the per-element gather that lost for the store-bound kernels: one
+// 32-bit read per output dword plus a byte permutation, with misaligned reads 1.8x slower,
+// with aligned pairs and a funnel shift 1.0-1.4x.)
+template <int E, int kCap, class Sink>
+__device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t lane, uint64_t word, uintptr_t vaddr,
                                             uint32_t cnt, uintptr_t vbeg, uintptr_t vend, Sink &sink) {
     using Sh = Shape<E>;
+    using WS = WaveScratch<E, kCap>;
+    const uint32_t pc = __popcll(word);
+    const uint32_t incl = wave_inclusive_scan(pc);
+    const uint32_t excl = incl - pc;
+    if (kCap < kTileElems) {
+        // more 1 bits than the staging area holds (decided on the bitmap itself, not on the
+        // table): stage and expand the tile one step at a time; a step has at most 1024 values
+        const uint32_t ones = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
+        if (ones > kCap) {  // wave-uniform
+            S.words[lane] = word;
+#pragma unroll
+            for (int k = 0; k < Sh::kSteps; ++k) {
+                // values before the step's first word; the step's own count
+                const uint32_t w0 = k * Sh::kLaneElems;
+                const uint32_t first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(4 * w0, static_cast<int>(excl)));
+                const uint32_t last = static_cast<uint32_t>(
+                    __builtin_amdgcn_ds_bpermute(4 * (w0 + Sh::kLaneElems - 1), static_cast<int>(incl)));
+                const uintptr_t va = vaddr + uintptr_t(E) * first;
+                const uintptr_t a16 = va & ~uintptr_t(15);
+                const uint32_t shift = static_cast<uint32_t>(va - a16) / E;
+                const uint32_t n = last - first;  // <= 1024 <= kCap
+                const uint32_t nch = n ? (((shift + n) * E + 15) >> 4) : 0;
+                S.start[lane] = excl - first + shift;  // meaningful for the step's words only
+                for (uint32_t ch = lane; ch < nch; ch += 64)
+                    S.stage[ch] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
+                wave_lds_sync();
+                expand_step<E, kCap>(S, k, lane, sink);
+                wave_lds_sync();
+            }
+            return;
+        }
+    }
     // --- issue the loads of the tile's value slice (16-byte units from the 16-byte
     //     boundary at or below its first value)
     const uintptr_t a16 = vaddr & ~uintptr_t(15);
     const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
-    cnt = cnt > kTileElems ? kTileElems : cnt;  // a stale or foreign table must not overrun the staging area
+    cnt = cnt > kCap ? kCap : cnt;  // a stale or foreign table must not overrun the staging area
     const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
-    u32x4 r[Sh::kStageRounds];
+    u32x4 r[WS::kStageRounds];
 #pragma unroll
-    for (int q = 0; q < Sh::kStageRounds; ++q) {
+    for (int q = 0; q < WS::kStageRounds; ++q) {
         const uint32_t ch = q * 64 + lane;
         if (ch < nch) r[q] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
     }
-
-    // --- popcount of this lane's word, scan across the wave
-    const uint32_t pc = __popcll(word);
-    const uint32_t incl = wave_inclusive_scan(pc);
     S.words[lane] = word;
-    S.start[lane] = incl - pc + shift;
+    S.start[lane] = excl + shift;
 #pragma unroll
-    for (int q = 0; q < Sh::kStageRounds; ++q) {
+    for (int q = 0; q < WS::kStageRounds; ++q) {
         const uint32_t ch = q * 64 + lane;
         if (ch < nch) S.stage[ch] = r[q];
     }
-    // LDS operations of one wave execute in issue order, so the reads below see the
-    // writes above; the fences only keep the compiler from moving them.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // --- expand: per step every lane turns kLaneElems bitmap bits into 16 bytes of output
+    wave_lds_sync();
 #pragma unroll
-    for (int k = 0; k < Sh::kSteps; ++k) {
-        const uint32_t wi = k * Sh::kLaneElems + lane / Sh::kLanesPerWord;
-        const uint64_t w = S.words[wi];
-        const uint32_t sh = (lane % Sh::kLanesPerWord) * Sh::kLaneElems;
-        const uint32_t bits = static_cast<uint32_t>(w >> sh) & ((1u << Sh::kLaneElems) - 1);
-        const uint32_t s = S.start[wi] + __popcll(w & ((uint64_t(1) << sh) - 1));
-        // every element is read from the staging area at its rank; the ones whose bit is 0
-        // pick up a neighbour's value and are masked to the all-zero pattern.  (Measured
-        // alternatives that lost: one 32-bit read per output dword plus a byte permutation,
-        // with misaligned reads 1.8x slower, with aligned pairs and a funnel shift 1.0-1.4x.)
-        u32x4 d;
-        if (E == 2) {
-            const uint16_t *sp = reinterpret_cast<const uint16_t *>(S.stage) + s;
-            uint32_t h[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
-            d.x = (h[0] | (h[1] << 16)) & half_mask(bits);
-            d.y = (h[2] | (h[3] << 16)) & half_mask(bits >> 2);
-            d.z = (h[4] | (h[5] << 16)) & half_mask(bits >> 4);
-            d.w = (h[6] | (h[7] << 16)) & half_mask(bits >> 6);
-        } else {
-            const uint8_t *sp = reinterpret_cast<const uint8_t *>(S.stage) + s;
-            uint32_t h[16];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
-            d.x = (h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24)) & byte_mask(bits);
-            d.y = (h[4] | (h[5] << 8) | (h[6] << 16) | (h[7] << 24)) & byte_mask(bits >> 4);
-            d.z = (h[8] | (h[9] << 8) | (h[10] << 16) | (h[11] << 24)) & byte_mask(bits >> 8);
-            d.w = (h[12] | (h[13] << 8) | (h[14] << 16) | (h[15] << 24)) & byte_mask(bits >> 12);
-        }
-        sink(k, (k * 64 + lane) * Sh::kLaneElems, d);
-    }
+    for (int k = 0; k < Sh::kSteps; ++k) expand_step<E, kCap>(S, k, lane, sink);
     // the next tile's LDS writes must stay behind this tile's LDS reads
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    wave_lds_sync();
 }
 
 // ---------------------------------------------------------------- tile expander, window form
@@ -504,9 +551,12 @@ __device__ __forceinline__ void expand_tile_window(WindowScratch<kSeg> &S, const
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int E, bool kAlignedOut, bool kBurst>
+// kSparse: the variant for store-dominated matrices (fewer than one element in five kept): the
+// small staging area and all stores of a tile released together.
+template <int E, bool kAlignedOut, bool kSparse>
 __global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
-    __shared__ WaveScratch<E> s_scratch;
+    constexpr bool kBurst = kSparse;
+    __shared__ WaveScratch<E, kSparse ? 1024 : kTileElems> s_scratch;
     const uint32_t gc = blockIdx.x / kTilesPerChunk;
     const uint32_t tl = blockIdx.x % kTilesPerChunk;  // tile, relative to the chunk
     const MatParams &M = P.m[find_matrix(P, gc)];

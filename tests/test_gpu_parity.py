@@ -359,6 +359,43 @@ def test_decompress_u8_matches_oracle(shape, keep):
     assert np.array_equal(out.cpu().numpy(), expect)
 
 
+@pytest.mark.parametrize("wide", [True, False], ids=["fp16", "u8"])
+def test_dense_tiles_inside_a_sparse_matrix(wide):
+    """A matrix sparse enough overall for the small-staging expander that still holds tiles with
+    more 1 bits than that staging area takes: all 4096 set, 1025 (one over), exactly 1024 (the
+    limit), a dense run across a tile boundary, and a dense ragged last tile."""
+    rows, cols = 64, 4099
+    n = rows * cols
+    _say(f"dense tiles in a sparse matrix wide={wide}")
+    g = np.random.default_rng(77 + wide)
+    bits = g.random(n) < 0.05
+    bits[3 * 4096:4 * 4096] = True
+    for tile, ones in ((7, 1025), (9, 1024), (12, 2500), (13, 4095)):
+        t = np.zeros(4096, bool)
+        t[g.choice(4096, ones, replace=False)] = True
+        bits[tile * 4096:(tile + 1) * 4096] = t
+    bits[20 * 4096 - 700:20 * 4096 + 900] = True
+    bits[(n // 4096) * 4096:] = True
+    assert bits.sum() * 5 < n
+    bitmap = np.zeros(endor.bitmap_bytes(rows, cols), np.uint8)
+    packed = np.packbits(bits, bitorder="little")
+    bitmap[: packed.size] = packed
+    nnz = int(bits.sum())
+    if wide:
+        values = g.integers(0, 1 << 16, size=nnz, dtype=np.uint32).astype(np.uint16)
+    else:
+        values = g.integers(0, 256, size=nnz, dtype=np.uint16).astype(np.uint8)
+    c = endor.Compressed(rows, cols, bitmap, values, None)
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    m = endor.to_device(c)
+    out = torch.full((rows, cols), 0x5A, dtype=torch.int16 if wide else torch.uint8, device="cuda")
+    for _ in range(2):
+        endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got.view(np.uint16) if wide else got, expect)
+
+
 @pytest.mark.parametrize("voff", [1, 5, 15])
 @pytest.mark.parametrize("ooff", [0, 1, 8])
 def test_u8_unaligned_values_and_output(voff, ooff):
