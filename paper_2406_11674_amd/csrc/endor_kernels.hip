@@ -212,6 +212,17 @@ struct alignas(16) WaveScratch {
     uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
 };
 
+// 16 bytes per lane from global memory straight into LDS: lane l writes lds_base + 16*l
+// (lds_base is wave-uniform; lanes that are switched off write nothing).  kStreamed marks the
+// load non-temporal.
+template <bool kStreamed = true>
+__device__ __forceinline__ void load_to_lds16(const u32x4 *src, u32x4 *lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, kStreamed ? 2 : 0);
+}
+// Every load this wave has issued is complete, those into LDS included (s_waitcnt vmcnt(0)).
+__device__ __forceinline__ void wait_loads_to_lds() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
 template <int E>
 __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
@@ -254,6 +265,8 @@ struct StoreSink {
     uint8_t *out;     // byte address of the tile's first output element
     uint32_t nvalid;  // elements of the tile that exist (<= 4096)
     u32x4 held[kBurst ? Shape<E>::kSteps : 1];
+    // how far a loop over the steps must be unrolled for `held` to stay in registers
+    static constexpr int kStepUnroll = kBurst ? Shape<E>::kSteps : 1;
     __device__ __forceinline__ void put(uint32_t le, u32x4 d) const {
         __builtin_nontemporal_store(d, reinterpret_cast<u32x4 *>(out + size_t(le) * E));
     }
@@ -355,7 +368,7 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
         const uint32_t ones = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
         if (ones > kCap) {  // wave-uniform
             S.words[lane] = word;
-#pragma unroll
+#pragma unroll Sink::kStepUnroll
             for (int k = 0; k < Sh::kSteps; ++k) {
                 // values before the step's first word; the step's own count
                 const uint32_t w0 = k * Sh::kLaneElems;
@@ -383,18 +396,24 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
     const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
     cnt = cnt > kCap ? kCap : cnt;  // a stale or foreign table must not overrun the staging area
     const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
-    u32x4 r[WS::kStageRounds];
+    if (nch != 0 && a16 >= vbeg && a16 + 16 * uintptr_t(nch) <= vend) {  // the whole slice lies inside `values`
+        // Straight from memory into the staging area (global_load_lds_dwordx4: lane l of an
+        // instruction deposits its 16 bytes at the LDS address in M0 plus 16*l), no registers
+        // in between.  Values are read once: streamed past the caches.
+        S.words[lane] = word;
+        S.start[lane] = excl + shift;
 #pragma unroll
-    for (int q = 0; q < WS::kStageRounds; ++q) {
-        const uint32_t ch = q * 64 + lane;
-        if (ch < nch) r[q] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
-    }
-    S.words[lane] = word;
-    S.start[lane] = excl + shift;
-#pragma unroll
-    for (int q = 0; q < WS::kStageRounds; ++q) {
-        const uint32_t ch = q * 64 + lane;
-        if (ch < nch) S.stage[ch] = r[q];
+        for (int q = 0; q < WS::kStageRounds; ++q) {
+            const uint32_t ch = q * 64 + lane;
+            if (ch < nch) load_to_lds16(reinterpret_cast<const u32x4 *>(a16) + ch, &S.stage[q * 64]);
+        }
+        wait_loads_to_lds();
+    } else {  // the first or last tile of an array that does not begin and end on 16-byte boundaries
+        S.words[lane] = word;
+        S.start[lane] = excl + shift;
+#pragma unroll 1
+        for (uint32_t ch = lane; ch < nch; ch += 64)
+            S.stage[ch] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
     }
     wave_lds_sync();
 #pragma unroll
@@ -551,12 +570,11 @@ __device__ __forceinline__ void expand_tile_window(WindowScratch<kSeg> &S, const
     __builtin_amdgcn_wave_barrier();
 }
 
-// kSparse: the variant for store-dominated matrices (fewer than one element in five kept): the
-// small staging area and all stores of a tile released together.
-template <int E, bool kAlignedOut, bool kSparse>
+// kCap: values the staging area holds (the host picks it from the batch's density); kBurst: all
+// stores of a tile released together (for store-dominated matrices).
+template <int E, bool kAlignedOut, int kCap, bool kBurst>
 __global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
-    constexpr bool kBurst = kSparse;
-    __shared__ WaveScratch<E, kSparse ? 1024 : kTileElems> s_scratch;
+    __shared__ WaveScratch<E, kCap> s_scratch;
     const uint32_t gc = blockIdx.x / kTilesPerChunk;
     const uint32_t tl = blockIdx.x % kTilesPerChunk;  // tile, relative to the chunk
     const MatParams &M = P.m[find_matrix(P, gc)];
@@ -1191,11 +1209,11 @@ template <int E>
 void launch_expand(const Group &g, hipStream_t s) {
     const dim3 grid(g.chunks * kTilesPerChunk);
     if (!g.aligned_out)
-        hipLaunchKernelGGL((endor_expand_kernel<E, false, false>), grid, dim3(64), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, false, kTileElems, false>), grid, dim3(64), 0, s, g.P);
     else if (g.nnz * 5 < g.elems)  // fewer than one element in five kept: store-dominated
-        hipLaunchKernelGGL((endor_expand_kernel<E, true, true>), grid, dim3(64), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, true, 1024, true>), grid, dim3(64), 0, s, g.P);
     else
-        hipLaunchKernelGGL((endor_expand_kernel<E, true, false>), grid, dim3(64), 0, s, g.P);
+        hipLaunchKernelGGL((endor_expand_kernel<E, true, kTileElems, false>), grid, dim3(64), 0, s, g.P);
 }
 
 // The shared driver of every device entry point.  `mats` holds 16-bit typed pointers;
