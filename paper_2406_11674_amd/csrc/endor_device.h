@@ -1,6 +1,7 @@
 // Wave-level building blocks shared by the device code of the Endor library (gfx950, wave64):
-// prefix sums across the lanes of a wave with DPP row shifts and broadcasts, and the lookup of
-// a chunk's absolute start from the per-chunk totals of the offset table.
+// prefix sums across the lanes of a wave with DPP row shifts and broadcasts, the lookup of
+// a chunk's absolute start from the per-chunk totals of the offset table, and the window
+// form of the expansion used by the fused products.
 #ifndef ENDOR_DEVICE_H_
 #define ENDOR_DEVICE_H_
 
@@ -49,6 +50,107 @@ __device__ __forceinline__ uint64_t chunk_base(const uint32_t *chunk_total, uint
     const uint32_t lo = wave_sum(part & 0xffffu);
     const uint32_t hi = wave_sum(part >> 16);
     return uint64_t(lo) + (uint64_t(hi) << 16);
+}
+
+// ---------------------------------------------------------------- expansion of 16-bit values, window form
+//
+// For the kernels that consume the expanded elements in registers (the products): the values
+// a bitmap byte consumes are consecutive in `values`, at most 8 of them, so a lane reads that
+// window of 16 bytes straight from memory (neighbouring lanes' windows overlap, the cache
+// serves the overlap) and moves the values to their positions with v_perm_b32, whose
+// selectors depend on the byte's bit pattern only and come from tables in LDS:
+//     out dword 0 <- perm(w0, w0), dword 1 <- perm(w1, w0),
+//     dword 2, 3  <- perm(w1, w0) | perm(w3, w2)        (w0..w3: the window, 8 halves)
+// Element j of the byte takes window half popcount(bits below j); a selector byte of 0x0c
+// yields zero, which also serves as the mask for 0 bits.  No staging of values in LDS and no
+// per-element gathers: measured against an LDS-staged window (three two-dword LDS reads per
+// byte) and against eight 2-byte LDS gathers per byte, this form is the fastest of the three.
+
+struct alignas(16) WindowTables {
+    u32x4 sel23[256];    // per byte pattern: selA, selB of output dword 2; selA, selB of dword 3
+    uint64_t sel01[16];  // per low nibble: selectors of output dwords 0 and 1
+};
+
+// selector bytes that copy half k (0..3) of the 64-bit source pair {hi, lo} of a v_perm_b32
+__device__ __forceinline__ uint32_t half_selector(uint32_t k) { return ((2 * k + 1) << 8) | (2 * k); }
+
+// Fill the tables: thread t of the (at least 256-thread) workgroup writes the entry of pattern t.
+__device__ __forceinline__ void window_tables_init(WindowTables &T, uint32_t t) {
+    if (t < 256) {
+        uint32_t sel[4] = {0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu};  // A2, B2, A3, B3
+#pragma unroll
+        for (int e = 4; e < 8; ++e) {
+            if ((t >> e) & 1) {
+                const uint32_t k = __popc(t & ((1u << e) - 1));  // window half this element takes: 0..7
+                const int which = 2 * ((e - 4) >> 1) + (k >= 4 ? 1 : 0);
+                const uint32_t hs = half_selector(k & 3) ^ 0x0c0cu;  // XOR turns the 0x0c0c placeholder into it
+                sel[which] ^= hs << (16 * (e & 1));
+            }
+        }
+        u32x4 v;
+        v.x = sel[0];
+        v.y = sel[1];
+        v.z = sel[2];
+        v.w = sel[3];
+        T.sel23[t] = v;
+    }
+    if (t < 16) {
+        uint32_t s01[2] = {0x0c0c0c0cu, 0x0c0c0c0cu};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if ((t >> e) & 1) {
+                const uint32_t k = __popc(t & ((1u << e) - 1));  // 0..3
+                s01[e >> 1] ^= (half_selector(k) ^ 0x0c0cu) << (16 * (e & 1));
+            }
+        }
+        T.sel01[t] = uint64_t(s01[0]) | (uint64_t(s01[1]) << 32);
+    }
+}
+
+// The window's values moved to the positions of the 1 bits of `bits` (a bitmap byte); 0 elsewhere.
+__device__ __forceinline__ u32x4 place_window(const WindowTables &T, uint32_t bits, u32x4 w) {
+    const uint64_t s01 = T.sel01[bits & 15u];
+    const u32x4 s23 = T.sel23[bits];
+    u32x4 d;
+    d.x = __builtin_amdgcn_perm(w.x, w.x, static_cast<uint32_t>(s01));
+    d.y = __builtin_amdgcn_perm(w.y, w.x, static_cast<uint32_t>(s01 >> 32));
+    d.z = __builtin_amdgcn_perm(w.y, w.x, s23.x) | __builtin_amdgcn_perm(w.w, w.z, s23.y);
+    d.w = __builtin_amdgcn_perm(w.y, w.x, s23.z) | __builtin_amdgcn_perm(w.w, w.z, s23.w);
+    return d;
+}
+
+// The 16 bytes (8 values of 16 bits) at byte address p, which is 2-byte aligned only; bytes
+// outside [vbeg, vend) read as 0.  Read as the 20 bytes from the dword boundary below p and
+// shifted into place: a load whose address is not a multiple of 4 costs the cache nearly
+// twice the accesses (measured).  Normal cached loads: the windows overlap.
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+__device__ __forceinline__ u32x4 load_window16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
+    const uintptr_t a4 = p & ~uintptr_t(3);
+    if (a4 >= vbeg && a4 + 20 <= vend) {
+        const u32x4 d = *reinterpret_cast<const u32x4_a4 *>(a4);
+        const uint32_t sh = static_cast<uint32_t>(p) & 3u;  // 0 or 2
+        const uint32_t d4 = *reinterpret_cast<const uint32_t *>(a4 + 16);  // the last value of a shifted window
+        u32x4 w;
+        w.x = __builtin_amdgcn_alignbyte(d.y, d.x, sh);
+        w.y = __builtin_amdgcn_alignbyte(d.z, d.y, sh);
+        w.z = __builtin_amdgcn_alignbyte(d.w, d.z, sh);
+        w.w = __builtin_amdgcn_alignbyte(d4, d.w, sh);
+        return w;
+    }
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uintptr_t q = p + 2 * j;
+        uint32_t v = 0;
+        if (q >= vbeg && q + 2 <= vend) v = *reinterpret_cast<const uint16_t *>(q);
+        d[j >> 1] |= v << (16 * (j & 1));
+    }
+    u32x4 r;
+    r.x = d[0];
+    r.y = d[1];
+    r.z = d[2];
+    r.w = d[3];
+    return r;
 }
 
 }  // namespace endor_device

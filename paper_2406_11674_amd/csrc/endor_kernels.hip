@@ -45,6 +45,10 @@ namespace {
 
 using endor_device::chunk_base;
 using endor_device::dpp_or_zero;
+using endor_device::load_window16;
+using endor_device::place_window;
+using endor_device::window_tables_init;
+using endor_device::WindowTables;
 using endor_device::row_inclusive_scan;
 using endor_device::u32x4;
 using endor_device::wave_inclusive_scan;
@@ -422,154 +426,6 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
     wave_lds_sync();
 }
 
-// ---------------------------------------------------------------- tile expander, window form
-//
-// The same job as expand_tile (16-bit elements), arranged for the kernels that are bound by
-// the expansion work itself rather than by memory traffic (the products, where nothing is
-// stored).  Instead of eight 2-byte LDS gathers per step, a lane reads the window of the
-// (at most 8) values its bitmap byte consumes - 20 bytes from the dword boundary below the
-// first one, as three two-dword reads - shifts it into place with v_alignbyte_b32 and moves
-// the values to their positions with v_perm_b32, whose selectors depend on the byte's bit
-// pattern only and come from tables in LDS:
-//     out dword 0 <- perm(w0, w0), dword 1 <- perm(w1, w0),
-//     dword 2, 3  <- perm(w1, w0) | perm(w3, w2)        (w0..w3: the window, 8 halves)
-// (element j of the byte takes window half popcount(bits below j); a selector byte of 0x0c
-// yields zero, which also serves as the mask for 0 bits).  Per byte of bitmap the wave keeps
-// one table entry: (byte offset of its first value in the staging area) << 8 | the byte.
-// About half the VALU instructions and a third of the LDS cycles of the gather form.
-
-struct alignas(16) WindowTables {
-    u32x4 sel23[256];    // per byte pattern: selA, selB of output dword 2; selA, selB of dword 3
-    uint64_t sel01[16];  // per low nibble: selectors of output dwords 0 and 1
-};
-
-// selector bytes that copy half k (0..3) of the 64-bit source pair {hi, lo} of a v_perm_b32
-__device__ __forceinline__ uint32_t half_selector(uint32_t k) { return ((2 * k + 1) << 8) | (2 * k); }
-
-// Fill the tables: thread t of the (at least 256-thread) workgroup writes the entry of pattern t.
-__device__ __forceinline__ void window_tables_init(WindowTables &T, uint32_t t) {
-    if (t < 256) {
-        uint32_t sel[4] = {0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu};  // A2, B2, A3, B3
-#pragma unroll
-        for (int e = 4; e < 8; ++e) {
-            if ((t >> e) & 1) {
-                const uint32_t k = __popc(t & ((1u << e) - 1));  // window half this element takes: 0..7
-                const int which = 2 * ((e - 4) >> 1) + (k >= 4 ? 1 : 0);
-                const uint32_t hs = half_selector(k & 3) ^ 0x0c0cu;  // XOR turns the 0x0c0c placeholder into it
-                sel[which] ^= hs << (16 * (e & 1));
-            }
-        }
-        u32x4 v;
-        v.x = sel[0];
-        v.y = sel[1];
-        v.z = sel[2];
-        v.w = sel[3];
-        T.sel23[t] = v;
-    }
-    if (t < 16) {
-        uint32_t s01[2] = {0x0c0c0c0cu, 0x0c0c0c0cu};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if ((t >> e) & 1) {
-                const uint32_t k = __popc(t & ((1u << e) - 1));  // 0..3
-                s01[e >> 1] ^= (half_selector(k) ^ 0x0c0cu) << (16 * (e & 1));
-            }
-        }
-        T.sel01[t] = uint64_t(s01[0]) | (uint64_t(s01[1]) << 32);
-    }
-}
-
-// kSeg: positions a call covers (4096, or 2048 = the first 32 lanes' words; a smaller segment
-// halves the LDS a wave holds, so twice as many waves fit a compute unit).
-template <int kSeg>
-struct alignas(16) WindowScratch {
-    static constexpr int kChunks = (2 * (2 * 7 + kSeg) + 15) / 16 + 2;  // slice + slack + room for a window read past its end
-    static constexpr int kRounds = (kChunks - 2 + 63) / 64;
-    u32x4 stage[kChunks];      // the segment's slice of `values`
-    uint32_t entry[kSeg / 8];  // per bitmap byte: staging byte offset of its first value << 8 | byte
-};
-
-// Expand one segment of 16-bit elements with one wave; arguments as for expand_tile (lanes at or
-// past kSeg/64 pass word = 0).  The sink's step index runs over kSeg/512 steps.
-template <int kSeg, class Sink>
-__device__ __forceinline__ void expand_tile_window(WindowScratch<kSeg> &S, const WindowTables &T, uint32_t lane,
-                                                   uint64_t word, uintptr_t vaddr, uint32_t cnt, uintptr_t vbeg,
-                                                   uintptr_t vend, Sink &sink) {
-    using WS = WindowScratch<kSeg>;
-    const uintptr_t a16 = vaddr & ~uintptr_t(15);
-    const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / 2;  // elements of slack in front
-    cnt = cnt > kSeg ? kSeg : cnt;  // a stale or foreign table must not overrun the staging area
-    const uint32_t nch = cnt ? (((shift + cnt) * 2 + 15) >> 4) : 0;  // <= kChunks - 2
-    u32x4 r[WS::kRounds];
-#pragma unroll
-    for (int q = 0; q < WS::kRounds; ++q) {
-        const uint32_t ch = q * 64 + lane;
-        if (ch < nch) r[q] = load_values16<2>(a16 + 16 * uintptr_t(ch), vbeg, vend);
-    }
-    // one entry per byte of this lane's word
-    const uint32_t pc = __popcll(word);
-    uint32_t at = 2 * (wave_inclusive_scan(pc) - pc + shift);  // byte offset of the word's first value
-    if (lane < kSeg / 64) {
-        uint32_t e8[8];
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const uint32_t byte = static_cast<uint32_t>(word >> (8 * b)) & 0xffu;
-            e8[b] = (at << 8) | byte;
-            at += 2 * __popc(byte);
-        }
-        u32x4 lo, hi;
-        lo.x = e8[0];
-        lo.y = e8[1];
-        lo.z = e8[2];
-        lo.w = e8[3];
-        hi.x = e8[4];
-        hi.y = e8[5];
-        hi.z = e8[6];
-        hi.w = e8[7];
-        reinterpret_cast<u32x4 *>(S.entry)[2 * lane] = lo;
-        reinterpret_cast<u32x4 *>(S.entry)[2 * lane + 1] = hi;
-    }
-#pragma unroll
-    for (int q = 0; q < WS::kRounds; ++q) {
-        const uint32_t ch = q * 64 + lane;
-        if (ch < nch) S.stage[ch] = r[q];
-    }
-    // LDS operations of one wave execute in issue order; the fences only pin the compiler
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    const uint8_t *stage = reinterpret_cast<const uint8_t *>(S.stage);
-#pragma unroll
-    for (int k = 0; k < kSeg / 512; ++k) {
-        const uint32_t e = S.entry[k * 64 + lane];
-        const uint32_t bits = e & 0xffu;
-        const uint32_t off = e >> 8;  // byte offset of the byte's first value: even
-        const uint32_t *win = reinterpret_cast<const uint32_t *>(stage + (off & ~3u));
-        const uint32_t sh = off & 3u;  // 0 or 2
-        const uint32_t d0 = win[0], d1 = win[1], d2 = win[2], d3 = win[3], d4 = win[4];
-        const uint32_t w0 = __builtin_amdgcn_alignbyte(d1, d0, sh);
-        const uint32_t w1 = __builtin_amdgcn_alignbyte(d2, d1, sh);
-        const uint32_t w2 = __builtin_amdgcn_alignbyte(d3, d2, sh);
-        const uint32_t w3 = __builtin_amdgcn_alignbyte(d4, d3, sh);
-        const uint64_t s01 = T.sel01[bits & 15u];
-        const u32x4 s23 = T.sel23[bits];
-        u32x4 d;
-        d.x = __builtin_amdgcn_perm(w0, w0, static_cast<uint32_t>(s01));
-        d.y = __builtin_amdgcn_perm(w1, w0, static_cast<uint32_t>(s01 >> 32));
-        d.z = __builtin_amdgcn_perm(w1, w0, s23.x) | __builtin_amdgcn_perm(w3, w2, s23.y);
-        d.w = __builtin_amdgcn_perm(w1, w0, s23.z) | __builtin_amdgcn_perm(w3, w2, s23.w);
-        sink(k, (k * 64 + lane) * 8, d);
-        // Keep the compiler from interleaving all steps: it would hold every step's window and
-        // selectors at once (about 170 registers, two waves per SIMD); two steps in flight hide
-        // the LDS latency just as well with half the registers.
-        if (k & 1) __builtin_amdgcn_sched_barrier(0);
-    }
-    // the next segment's LDS writes must stay behind this segment's LDS reads
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 // kCap: values the staging area holds (the host picks it from the batch's density); kBurst: all
 // stores of a tile released together (for store-dominated matrices).
 template <int E, bool kAlignedOut, int kCap, bool kBurst>
@@ -868,12 +724,18 @@ struct GemvParams {
 };
 
 // y[i] = sum_j W[i][j] * x[j] straight from the compressed form: the dense row is never
-// written.  One wave per row walks the row's 4096-column segments, expanding each into
-// registers exactly as the decompressor does and feeding the fp16 pairs to multiply-adds.
-// Elements whose bit is 0 enter as +0.0, as they would from the dense matrix.
-// (Letting a wave take several rows in turn, to reuse the x segment it holds in registers, was
-// measured slower: 143 against 77 us with four rows per wave on 28672 x 8192.  A wave's tiles run
-// one after the other, so what counts is the number of independent waves.)
+// written.  One wave per row walks the row's 4096-column segments.  Per segment: popcount and
+// scan the lane's bitmap word, leave one entry per bitmap byte in LDS ((values of the segment
+// before the byte) << 8 | the byte); then a lane takes the bytes lane, 64 + lane, ... in turn,
+// reads each byte's window of values straight from memory, places the values by the byte's
+// bit pattern and feeds the fp16 pairs to multiply-adds against the matching 8 entries of x.
+// Elements whose bit is 0 enter as +0.0, as they would from the dense matrix.  The next
+// segment's bitmap word is loaded before the current one is worked on.
+// (Measured alternatives on 28672 x 8192, half kept: values staged in LDS and gathered element
+// by element 83 us, staged and read as windows 76 us, this form 72 us; a wave taking four rows
+// in turn 143 us: a wave's segments run one after the other, so what counts is the number of
+// independent waves.  Counters of this form: the vector cache handles some 530 line accesses
+// per segment where 200 would do if no two lanes shared a line.)
 constexpr int kGemvSeg = 4096;  // columns a wave expands at a time
 
 // kFastX: x is 16-byte aligned and cols a multiple of 8, so every lane's 8 entries of x are one
@@ -882,13 +744,14 @@ constexpr int kGemvSeg = 4096;  // columns a wave expands at a time
 template <bool kFastX>
 __global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
     __shared__ WindowTables s_tables;
-    __shared__ WindowScratch<kGemvSeg> s_scratch[kWaves];
+    __shared__ uint32_t s_entry[kWaves][kGemvSeg / 8];
     window_tables_init(s_tables, threadIdx.x);
     __syncthreads();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
     const int64_t i = int64_t(blockIdx.x) * kWaves + wave;
     if (i >= G.rows) return;  // whole wave; no workgroup barrier follows
+    uint32_t *entry = s_entry[wave];
     const int64_t nwords = (G.rows * G.cols + 63) >> 6;
     const int64_t row_bit = i * G.cols;
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(G.values);
@@ -896,11 +759,42 @@ __global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
     uint64_t next_value = static_cast<uint64_t>(G.row_offsets[i]);
     GemvSink sink;
     sink.acc = 0.0f;
+    uint64_t word = 0;
+    if (G.cols > 0)
+        word = segment_word(G.bitmap, nwords, row_bit, G.cols < kGemvSeg ? static_cast<uint32_t>(G.cols) : uint32_t(kGemvSeg), lane);
     for (int64_t c0 = 0; c0 < G.cols; c0 += kGemvSeg) {
         const int64_t left = G.cols - c0;
         const uint32_t nbits = left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg);
-        const uint64_t word = segment_word(G.bitmap, nwords, row_bit + c0, nbits, lane);
-        const uint32_t cnt = wave_sum(__popcll(word));
+        uint64_t next_word = 0;
+        if (left > kGemvSeg) {
+            const int64_t l2 = left - kGemvSeg;
+            next_word = segment_word(G.bitmap, nwords, row_bit + c0 + kGemvSeg,
+                                     l2 < kGemvSeg ? static_cast<uint32_t>(l2) : uint32_t(kGemvSeg), lane);
+        }
+        const uint32_t pc = __popcll(word);
+        const uint32_t incl = wave_inclusive_scan(pc);
+        const uint32_t cnt = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
+        {
+            uint32_t at = incl - pc;  // values of the segment before this lane's word
+            uint32_t e8[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const uint32_t byte = static_cast<uint32_t>(word >> (8 * b)) & 0xffu;
+                e8[b] = (at << 8) | byte;
+                at += __popc(byte);
+            }
+            u32x4 lo, hi;
+            lo.x = e8[0];
+            lo.y = e8[1];
+            lo.z = e8[2];
+            lo.w = e8[3];
+            hi.x = e8[4];
+            hi.y = e8[5];
+            hi.z = e8[6];
+            hi.w = e8[7];
+            reinterpret_cast<u32x4 *>(entry)[2 * lane] = lo;
+            reinterpret_cast<u32x4 *>(entry)[2 * lane + 1] = hi;
+        }
 #pragma unroll
         for (int k = 0; k < kGemvSeg / 512; ++k) {
             const uint32_t le = (k * 64 + lane) * 8;
@@ -919,8 +813,23 @@ __global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
                 sink.xs[k].w = h[6] | (h[7] << 16);
             }
         }
-        expand_tile_window<kGemvSeg>(s_scratch[wave], s_tables, lane, word, vbeg + 2 * next_value, cnt, vbeg, vend, sink);
+        wave_lds_sync();
+        const uintptr_t vseg = vbeg + 2 * next_value;
+        uint32_t e[kGemvSeg / 512];
+        u32x4 win[kGemvSeg / 512];
+#pragma unroll
+        for (int k = 0; k < kGemvSeg / 512; ++k) e[k] = entry[k * 64 + lane];
+#pragma unroll
+        for (int k = 0; k < kGemvSeg / 512; ++k)
+            win[k] = load_window16(vseg + 2 * uintptr_t(e[k] >> 8), vbeg, vend);
+#pragma unroll
+        for (int k = 0; k < kGemvSeg / 512; ++k) {
+            const u32x4 d = place_window(s_tables, e[k] & 0xffu, win[k]);
+            sink(k, 0, d);
+        }
+        wave_lds_sync();  // the next segment's entries stay behind this segment's reads
         next_value += cnt;
+        word = next_word;
     }
     const float total = wave_sum_f32(sink.acc);
     if (lane == 0) G.y[i] = total;
