@@ -52,6 +52,17 @@ __device__ __forceinline__ uint64_t chunk_base(const uint32_t *chunk_total, uint
     return uint64_t(lo) + (uint64_t(hi) << 16);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l writes lds_base + 16*l
+// (lds_base is wave-uniform; lanes that are switched off write nothing).  kStreamed marks the
+// load non-temporal.
+template <bool kStreamed = true>
+__device__ __forceinline__ void load_to_lds16(const u32x4 *src, u32x4 *lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, kStreamed ? 2 : 0);
+}
+// Every load this wave has issued is complete, those into LDS included (s_waitcnt vmcnt(0)).
+__device__ __forceinline__ void wait_loads_to_lds() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // ---------------------------------------------------------------- expansion of 16-bit values, window form
 //
 // For the kernels that consume the expanded elements in registers (the products): the values

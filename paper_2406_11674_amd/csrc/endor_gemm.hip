@@ -14,23 +14,26 @@
 //
 // A round, for the lane that is (row r = l/4, word j = l%4) while loading and
 // (row l%16, column block l/16) while multiplying:
-//   1. load the lane's 64 bitmap bits of the segment; popcount; prefix over the row's four
-//      words (DPP quad broadcasts).  Each row has its own cursor into `values` (its 1 bits
-//      so far), so the 16 rows are 16 independent streams.
-//   2. load the rows' value slices for the segment: 16-byte units from the 16-byte boundary
-//      below each cursor.  For this the lanes regroup as eight per row (rows l/8 and 8 + l/8),
-//      so that a load instruction fetches whole 128-byte lines (with four lanes per row and
-//      64-byte pieces the counters showed 1.4 times the bytes fetched); five rounds cover the
-//      worst case of 256 values.  Guarded so that nothing outside values[0, nnz) is read.  The
-//      units go to the rows' staging areas in LDS.
-//   3. per bitmap byte, one table entry: (offset of the byte's first value in the staging
-//      area) << 8 | the byte.
-//   4. eight steps: read the entry of (row, byte), look the byte up in a table built once
-//      per wave (the rank of every bit inside the byte), gather the 8 candidate values with
-//      2-byte LDS reads, merge-and-mask them with 4 v_perm_b32 whose selectors are formed from
-//      the bits, and issue the matrix instruction against the 16-byte fragment of X.
-// The loads of round t+1 (bitmap, values, X) are issued before the steps of round t, so a
-// wave keeps memory traffic in flight while it multiplies.
+//   1. the lane's 64 bitmap bits of the segment (loaded a round ahead); popcount; prefix over
+//      the row's four words (DPP quad broadcasts).  Each row has its own cursor into `values`
+//      (its 1 bits so far), so the 16 rows are 16 independent streams.
+//   2. per bitmap byte, one table entry in LDS: (values of the row's segment before the byte)
+//      << 8 | the byte.
+//   3. eight steps: read the entry of (row, byte), read the byte's window of values (16 bytes
+//      from the row's cursor plus the entry's count) straight from memory, move the values to
+//      the positions of the 1 bits with v_perm_b32 (selectors from a table indexed by the
+//      byte), and issue the matrix instruction against the 16-byte fragment of X.
+// Values are not staged: the windows of a row's neighbouring bytes overlap and the vector
+// cache serves the overlap.  The expansion runs in the loading role's lane order, where the
+// four lanes of a quad read neighbouring windows of one row, and the expanded 16 bytes are
+// handed to the multiplying lane with ds_bpermute.  (An earlier form staged every row's slice
+// in LDS and gathered the values one by one: 126 / 138 us for 1 / 16 right-hand sides on
+// 28672 x 8192, bound by LDS; this one takes 98 / 122 us, bound by the rate at which the
+// vector cache accepts line accesses.)
+// X: the four waves of a workgroup work on neighbouring row groups and the same column
+// range; the round's 256 columns of all right-hand sides are brought to LDS once per
+// workgroup (global_load_lds_dwordx4, double buffered, one barrier per round) and every wave
+// reads its B operands from there.
 //
 // Work is split over rows (16 per wave) and, to have enough waves, over column ranges
 // (ksplit ranges per row group); the starting cursor of a row at a column range comes from
@@ -48,7 +51,13 @@
 namespace {
 
 using endor_device::chunk_base;
+using endor_device::load_to_lds16;
+using endor_device::load_window16;
+using endor_device::place_window;
+using endor_device::window_tables_init;
+using endor_device::WindowTables;
 using endor_device::u32x4;
+using endor_device::wait_loads_to_lds;
 using endor_device::wave_sum;
 using endor_layout::chunks_of;
 using endor_layout::chunk_total_bytes;
@@ -65,10 +74,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kRows = 16;               // rows of W per wave: the M of the matrix instruction
 constexpr int kSegCols = 256;           // columns per round
 constexpr int kSteps = kSegCols / 32;   // matrix instructions per round
-constexpr int kRounds = 5;              // rounds of value loads per half of the rows: 8 lanes x 5 units >= 33
-constexpr int kRowUnits = 8 * kRounds;  // staging units per row
 constexpr int kInfoStride = 36;         // dwords per row of the entry table (32 used; 36 spreads the LDS banks)
 constexpr int kMaxSplit = 16;           // column ranges per row group at most
+constexpr int kGemmWaves = 4;           // waves (row groups) per workgroup; they share the tile of X
+constexpr int kXPitch = 2 * kSegCols + 16;  // bytes between right-hand sides in the LDS tile of X: 132 dwords, so the
+                                            // 16-byte reads of eight lanes (eight right-hand sides) cover all 32 banks
 
 struct GemmParams {
     const uint64_t *bitmap;
@@ -84,41 +94,18 @@ struct GemmParams {
     uint32_t x_fast;          // every fragment of X is a 16-byte aligned, in-range load
 };
 
-// Staging rows are 584 bytes apart, not 576: the 16 rows advance through their slices in
-// step, so with a pitch that is a multiple of 64 bytes (half the LDS banks) the 2-byte gathers of the
-// 16 rows would pile onto the same few banks; 146 dwords (= 18 mod 32) put the rows on 16
-// different even banks.  The price: units are written as two 8-byte stores.
-constexpr int kRowPitch8 = 2 * kRowUnits + 1;  // 64-bit words per staging row
-
 struct alignas(16) GemmScratch {
-    uint64_t rank2[256];                // byte pattern -> 2 * (number of lower 1 bits), one byte per bit
-    uint64_t stage[kRows][kRowPitch8];  // the rows' value slices of the current segment
-    uint32_t info[kRows][kInfoStride];  // per (row, bitmap byte): staging offset of its first value << 8 | byte
+    WindowTables tables;  // selectors of the value placement, per byte pattern
+    // per wave and (row, bitmap byte): values of the row's segment before it << 8 | byte
+    uint32_t info[kGemmWaves][kRows][kInfoStride];
+    // the segment's 256 columns of the 16 right-hand sides, for this round and the next
+    alignas(16) uint8_t xt[2][ENDOR_GEMM_MAX_BATCH][kXPitch];
 };
 
 // value of lane `k` of each group of four lanes, in all four
 template <int k>
 __device__ __forceinline__ uint32_t quad_bcast(uint32_t x) {
     return static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(x), k * 0x55, 0xf, 0xf, false));
-}
-
-// 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
-__device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
-    if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-    uint32_t d[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uintptr_t q = p + 2 * j;
-        uint32_t v = 0;
-        if (q >= vbeg && q + 2 <= vend) v = *reinterpret_cast<const uint16_t *>(q);
-        d[j >> 1] |= v << (16 * (j & 1));
-    }
-    u32x4 r;
-    r.x = d[0];
-    r.y = d[1];
-    r.z = d[2];
-    r.w = d[3];
-    return r;
 }
 
 // 64 bits of the bitmap starting at bit position e, of which the first nbits (0..64) count
@@ -132,21 +119,14 @@ __device__ __forceinline__ uint64_t bits_at(const uint64_t *bitmap, int64_t nwor
     return word;
 }
 
-// what a lane has in flight for the coming round
-struct Round {
-    uint64_t word;      // the lane's 64 bitmap bits (row l/4, word l%4 of the segment)
-    u32x4 va[kRounds];  // units of the value slice of row l/8 ...
-    u32x4 vb[kRounds];  // ... and of row 8 + l/8 (value-loading role: unit q*8 + l%8 in round q)
-    uint32_t na, nb;    // units those two rows' slices span
-    uint32_t first2;    // 2 * (staging index of the first value of the lane's word)
-    u32x4 xb[kSteps];   // fragments of X (as multiplying lane: right-hand side l%16, column block l/16)
-};
-
-__global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
+__global__ __launch_bounds__(64 * kGemmWaves) void endor_gemm_f16_kernel(GemmParams G) {
     __shared__ GemmScratch S;
-    const uint32_t lane = threadIdx.x;
-    const uint32_t group = blockIdx.x / G.ksplit;  // 16 rows
-    const uint32_t split = blockIdx.x % G.ksplit;  // column range
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // a workgroup: kGemmWaves neighbouring groups of 16 rows, one column range.  A group past
+    // the last row still runs (with no valid row): its wave takes part in loading X.
+    const uint32_t group = (blockIdx.x / G.ksplit) * kGemmWaves + wave;
+    const uint32_t split = blockIdx.x % G.ksplit;
     const int64_t row0 = int64_t(group) * kRows;
     const int64_t n = G.rows * G.cols;
     const int64_t nwords = (n + 63) >> 6;
@@ -156,19 +136,8 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
     if (seg_end > total_segs) seg_end = total_segs;
     const int64_t c_begin = seg_begin * kSegCols;
 
-    // ---- the rank table, four byte patterns per lane
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const uint32_t pat = t * 64 + lane;
-        uint64_t rk = 0;
-        uint32_t below = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            rk |= uint64_t(2 * below) << (8 * j);
-            below += (pat >> j) & 1;
-        }
-        S.rank2[pat] = rk;
-    }
+    window_tables_init(S.tables, threadIdx.x);  // visible after the first round's barrier
+    uint32_t(*info)[kInfoStride] = S.info[wave];
 
     // ---- loading role: row lr = lane/4, word lj = lane%4 of a segment
     const uint32_t lr = lane >> 2, lj = lane & 3;
@@ -183,7 +152,7 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
     // whole wave counts the third for each row in turn; all loads go out before the first
     // result is needed, so the 16 lookups cost one trip to memory, not sixteen.
     uintptr_t cursor = vbeg;
-    if (c_begin < G.cols) {  // wave-uniform
+    if (c_begin < G.cols && row0 < G.rows) {  // wave-uniform
         const int64_t e_first = row0 * G.cols + c_begin;
         const uint32_t c_first = static_cast<uint32_t>(e_first >> 20);  // chunk = 2^20 positions
         int64_t last_row = row0 + kRows - 1;
@@ -242,101 +211,77 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
 
     // ---- multiplying role: row mr = lane%16 (A) / right-hand side mr (B), column block mq = lane/16
     const uint32_t mr = lane & 15, mq = lane >> 4;
-    const uint16_t *xrow = G.x + int64_t(mr) * G.ldx;
     const bool x_ok = static_cast<int32_t>(mr) < G.nb;
 
     // Shapes whose rows start on 64-bit word boundaries (cols a multiple of 64: every model
     // shape) read a lane's bitmap word with one aligned load; others funnel it out of two.
     const bool word_rows = (G.cols & 63) == 0;  // wave-uniform
     const uint64_t *my_words = G.bitmap + ((row_ok ? my_row : 0) * G.cols >> 6) + lj;
-    const uint16_t *x_lane = xrow + 8 * mq;
 
-    auto issue = [&](int64_t seg, Round &R) {
+    // this lane's 64 bitmap bits of a segment (loading role)
+    auto load_word = [&](int64_t seg) -> uint64_t {
+        const int64_t col = seg * kSegCols + 64 * lj;
+        if (word_rows) return (row_ok && col < G.cols) ? my_words[(seg * kSegCols) >> 6] : 0;
+        return row_ok ? bits_at(G.bitmap, nwords, my_row * G.cols + col, G.cols - col) : 0;
+    };
+
+    // Expansion happens in the loading role (a quad of lanes = four neighbouring bytes of one
+    // row, whose windows share cache lines; with the multiplying role's lane order every lane
+    // of a load would touch a line of its own, and the vector cache's access rate was the
+    // bound: 1400 accesses per round against 400).  The expanded 16 bytes then move to the lane
+    // that multiplies them: lane 16*j + r takes those of lane 4*r + j.
+    const int from_lane = static_cast<int>(4 * (4 * mr + mq));  // byte index for ds_bpermute
+
+    // The segment's 256 columns of X go to LDS once per workgroup: wave w brings the right-hand
+    // sides 4w .. 4w+3 (those below nb), 512 bytes each, with the first 32 lanes.
+    auto load_x_tile = [&](int64_t seg, uint32_t buf) {
         const int64_t c0 = seg * kSegCols;
-        const int64_t col = c0 + 64 * lj;
-        if (word_rows)
-            R.word = (row_ok && col < G.cols) ? my_words[c0 >> 6] : 0;
-        else
-            R.word = row_ok ? bits_at(G.bitmap, nwords, my_row * G.cols + col, G.cols - col) : 0;
-        const uint32_t pc = __popcll(R.word);
-        const uint32_t p0 = quad_bcast<0>(pc), p1 = quad_bcast<1>(pc), p2 = quad_bcast<2>(pc), p3 = quad_bcast<3>(pc);
-        const uint32_t before = (lj > 0 ? p0 : 0) + (lj > 1 ? p1 : 0) + (lj > 2 ? p2 : 0);
-        const uint32_t cnt = p0 + p1 + p2 + p3;  // <= 256
-        const uintptr_t a16 = cursor & ~uintptr_t(15);
-        const uint32_t shift = static_cast<uint32_t>(cursor - a16) >> 1;  // values of slack in front
-        const uint32_t nunits = cnt ? ((shift + cnt) * 2 + 15) >> 4 : 0;  // <= 33
-        R.first2 = 2 * (shift + before);
-        // a row slice that lies inside values[0, nnz) with its rounding to 16-byte units (all but
-        // the first and last few values of the array) needs no per-unit range checks
-        const bool inside = a16 >= vbeg && a16 + 16 * uintptr_t(nunits) <= vend;
-        const bool all_inside = __builtin_amdgcn_ballot_w64(!inside) == 0;  // wave-uniform
-        // Value-loading role: eight lanes per row, so that one load instruction fetches whole
-        // 128-byte lines (rows l/8 and 8 + l/8; their slice start and length come from the
-        // lanes that own the rows' cursors).
-        const uint32_t a_lo = static_cast<uint32_t>(a16), a_hi = static_cast<uint32_t>(a16 >> 32);
-        const int own_a = static_cast<int>(16 * (lane >> 3)), own_b = own_a + 128;  // byte index of lane 4*row
-        const uintptr_t base_a = (uintptr_t(static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, a_hi))) << 32) |
-                                 static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, a_lo));
-        const uintptr_t base_b = (uintptr_t(static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, a_hi))) << 32) |
-                                 static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, a_lo));
-        R.na = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_a, static_cast<int>(nunits)));
-        R.nb = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(own_b, static_cast<int>(nunits)));
-        const uint32_t sub = lane & 7;
-        if (all_inside) {
-            const u32x4 *pa = reinterpret_cast<const u32x4 *>(base_a) + sub;
-            const u32x4 *pb = reinterpret_cast<const u32x4 *>(base_b) + sub;
+        const bool whole = G.x_fast && c0 + kSegCols <= G.cols;  // aligned 16-byte pieces, all in range
 #pragma unroll
-            for (int q = 0; q < kRounds; ++q) {
-                if (uint32_t(q * 8) + sub < R.na) R.va[q] = __builtin_nontemporal_load(pa + q * 8);
-                if (uint32_t(q * 8) + sub < R.nb) R.vb[q] = __builtin_nontemporal_load(pb + q * 8);
-            }
-        } else {
+        for (int i = 0; i < ENDOR_GEMM_MAX_BATCH / kGemmWaves; ++i) {
+            const int b = static_cast<int>(wave) * (ENDOR_GEMM_MAX_BATCH / kGemmWaves) + i;
+            if (b < G.nb && lane < 32) {
+                const uint16_t *src = G.x + int64_t(b) * G.ldx + c0;
+                u32x4 *dst = reinterpret_cast<u32x4 *>(S.xt[buf][b]);
+                if (whole) {
+                    load_to_lds16<false>(reinterpret_cast<const u32x4 *>(src) + lane, dst);
+                } else {
+                    uint32_t h[8];
 #pragma unroll
-            for (int q = 0; q < kRounds; ++q) {
-                const uint32_t u = q * 8 + sub;
-                if (u < R.na) R.va[q] = load_values16(base_a + 16 * uintptr_t(u), vbeg, vend);
-                if (u < R.nb) R.vb[q] = load_values16(base_b + 16 * uintptr_t(u), vbeg, vend);
-            }
-        }
-        cursor += 2 * uintptr_t(cnt);
-        if (G.x_fast && c0 + kSegCols <= G.cols) {  // wave-uniform: every fragment is a whole aligned load
-#pragma unroll
-            for (int t = 0; t < kSteps; ++t) {
-                u32x4 f;
-                f.x = f.y = f.z = f.w = 0;
-                if (x_ok) f = *reinterpret_cast<const u32x4 *>(x_lane + c0 + 32 * t);
-                R.xb[t] = f;
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < kSteps; ++t) {
-                const int64_t c = c0 + 32 * t + 8 * mq;
-                uint32_t h[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) h[j] = (x_ok && c + j < G.cols) ? uint32_t(xrow[c + j]) : 0u;
-                u32x4 f;
-                f.x = h[0] | (h[1] << 16);
-                f.y = h[2] | (h[3] << 16);
-                f.z = h[4] | (h[5] << 16);
-                f.w = h[6] | (h[7] << 16);
-                R.xb[t] = f;
+                    for (int j = 0; j < 8; ++j) h[j] = (c0 + 8 * lane + j < G.cols) ? uint32_t(src[8 * lane + j]) : 0u;
+                    u32x4 f;
+                    f.x = h[0] | (h[1] << 16);
+                    f.y = h[2] | (h[3] << 16);
+                    f.z = h[4] | (h[5] << 16);
+                    f.w = h[6] | (h[7] << 16);
+                    dst[lane] = f;
+                }
             }
         }
     };
 
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    Round R;
-    if (seg_begin < seg_end) issue(seg_begin, R);
+    if (seg_begin < seg_end) load_x_tile(seg_begin, 0);
+    uint64_t word = seg_begin < seg_end ? load_word(seg_begin) : 0;
     for (int64_t seg = seg_begin; seg < seg_end; ++seg) {
-        // ---- land the round's loads in LDS: entries of the lane's 8 bitmap bytes, value units
+        const uint32_t buf = static_cast<uint32_t>(seg - seg_begin) & 1u;
+        // this wave's part of the round's tile of X has landed; after the barrier the whole tile
+        // has, and every wave is through the previous round (whose tile the next load overwrites)
+        wait_loads_to_lds();
+        __syncthreads();
+        if (seg + 1 < seg_end) load_x_tile(seg + 1, buf ^ 1u);
+        // ---- entries of the lane's 8 bitmap bytes
+        const uint32_t pc = __popcll(word);
+        const uint32_t p0 = quad_bcast<0>(pc), p1 = quad_bcast<1>(pc), p2 = quad_bcast<2>(pc), p3 = quad_bcast<3>(pc);
+        const uint32_t cnt = p0 + p1 + p2 + p3;  // values of the row's segment: <= 256
         {
+            uint32_t at = (lj > 0 ? p0 : 0) + (lj > 1 ? p1 : 0) + (lj > 2 ? p2 : 0);
             uint32_t e8[8];
-            uint32_t at2 = R.first2;
 #pragma unroll
             for (int b = 0; b < 8; ++b) {
-                const uint32_t byte = static_cast<uint32_t>(R.word >> (8 * b)) & 0xffu;
-                e8[b] = (at2 << 8) | byte;
-                at2 += 2 * __popc(byte);
+                const uint32_t byte = static_cast<uint32_t>(word >> (8 * b)) & 0xffu;
+                e8[b] = (at << 8) | byte;
+                at += __popc(byte);
             }
             u32x4 lo, hi;
             lo.x = e8[0];
@@ -347,89 +292,44 @@ __global__ __launch_bounds__(64) void endor_gemm_f16_kernel(GemmParams G) {
             hi.y = e8[5];
             hi.z = e8[6];
             hi.w = e8[7];
-            u32x4 *ip = reinterpret_cast<u32x4 *>(&S.info[lr][lj * 8]);
+            u32x4 *ip = reinterpret_cast<u32x4 *>(&info[lr][lj * 8]);
             ip[0] = lo;
             ip[1] = hi;
-            const uint32_t ra = lane >> 3, sub = lane & 7;
-#pragma unroll
-            for (int q = 0; q < kRounds; ++q) {
-                const uint32_t u = q * 8 + sub;
-                if (u < R.na) {
-                    S.stage[ra][2 * u] = uint64_t(R.va[q].x) | (uint64_t(R.va[q].y) << 32);
-                    S.stage[ra][2 * u + 1] = uint64_t(R.va[q].z) | (uint64_t(R.va[q].w) << 32);
-                }
-                if (u < R.nb) {
-                    S.stage[ra + 8][2 * u] = uint64_t(R.vb[q].x) | (uint64_t(R.vb[q].y) << 32);
-                    S.stage[ra + 8][2 * u + 1] = uint64_t(R.vb[q].z) | (uint64_t(R.vb[q].w) << 32);
-                }
-            }
-        }
-        // This round's fragments of X must have arrived before the next round's loads are
-        // issued: the hardware counts outstanding loads in order, so a wait placed after the
-        // new loads would wait for them as well.  The empty asm makes the values "used" here.
-        u32x4 xb[kSteps];
-#pragma unroll
-        for (int t = 0; t < kSteps; ++t) {
-            xb[t] = R.xb[t];
-            asm volatile("" : "+v"(xb[t].x), "+v"(xb[t].y), "+v"(xb[t].z), "+v"(xb[t].w));
         }
         // LDS operations of one wave execute in issue order; the fences only pin the compiler
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- next round's loads go out before this round's arithmetic
-        if (seg + 1 < seg_end) issue(seg + 1, R);
-
-        // ---- 8 steps: expand 8 elements of row mr, multiply.  The table reads of all steps go
-        //      out first, then the gathers two steps at a time, so that the LDS latencies of
-        //      different steps overlap.
-        const uint8_t *row_stage = reinterpret_cast<const uint8_t *>(&S.stage[mr][0]);
+        // ---- loads: the next segment's bitmap word, this segment's windows
+        const uint64_t next_word = seg + 1 < seg_end ? load_word(seg + 1) : 0;
         uint32_t entry[kSteps];
-        uint64_t rk[kSteps];
+        u32x4 win[kSteps];
 #pragma unroll
-        for (int t = 0; t < kSteps; ++t) entry[t] = S.info[mr][t * 4 + mq];
+        for (int t = 0; t < kSteps; ++t) entry[t] = info[lr][t * 4 + lj];
 #pragma unroll
-        for (int t = 0; t < kSteps; ++t) rk[t] = S.rank2[entry[t] & 0xffu];
+        for (int t = 0; t < kSteps; ++t) win[t] = load_window16(cursor + 2 * uintptr_t(entry[t] >> 8), vbeg, vend);
+
+        // ---- 8 steps: place the values of 8 elements of row lr, hand them to the multiplying lane, multiply
 #pragma unroll
-        for (int t0 = 0; t0 < kSteps; t0 += 2) {
-            uint32_t h[2][8];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint8_t *base = row_stage + (entry[t0 + u] >> 8);
-                const uint32_t rlo = static_cast<uint32_t>(rk[t0 + u]), rhi = static_cast<uint32_t>(rk[t0 + u] >> 32);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    h[u][j] = *reinterpret_cast<const uint16_t *>(base + ((rlo >> (8 * j)) & 0xffu));
-                    h[u][4 + j] = *reinterpret_cast<const uint16_t *>(base + ((rhi >> (8 * j)) & 0xffu));
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint32_t bits = entry[t0 + u] & 0xffu;
-                // v_perm_b32(hi, lo, sel): selector bytes 0,1 take lo's low half, 4,5 hi's low half
-                // and 0x0c gives 0, so sel = 0x0c0c0c0c with 0x0100 / 0x0504 put in where the bit
-                // is 1: XOR with 0x0d0c (low half) and 0x0908 (high half) under the sign-extended bits
-                uint32_t a4[4];
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const uint32_t m0 = static_cast<uint32_t>(static_cast<int32_t>(bits << (31 - 2 * d)) >> 31);
-                    const uint32_t m1 = static_cast<uint32_t>(static_cast<int32_t>(bits << (30 - 2 * d)) >> 31);
-                    const uint32_t sel = 0x0c0c0c0cu ^ (m0 & 0x00000d0cu) ^ (m1 & 0x09080000u);
-                    a4[d] = __builtin_amdgcn_perm(h[u][2 * d + 1], h[u][2 * d], sel);
-                }
-                u32x4 a;
-                a.x = a4[0];
-                a.y = a4[1];
-                a.z = a4[2];
-                a.w = a4[3];
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
-                                                             __builtin_bit_cast(f16x8, xb[t0 + u]), acc, 0, 0, 0);
-            }
+        for (int t = 0; t < kSteps; ++t) {
+            const u32x4 e = place_window(S.tables, entry[t] & 0xffu, win[t]);
+            u32x4 a;
+            a.x = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.x)));
+            a.y = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.y)));
+            a.z = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.z)));
+            a.w = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.w)));
+            u32x4 xb;  // 8 columns of right-hand side mr (rows of the tile at or past nb hold nothing)
+            xb.x = xb.y = xb.z = xb.w = 0;
+            if (x_ok) xb = *reinterpret_cast<const u32x4 *>(&S.xt[buf][mr][64 * t + 16 * mq]);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, xb), acc, 0,
+                                                         0, 0);
         }
         // the next round's LDS writes must stay behind this round's LDS reads
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        cursor += 2 * uintptr_t(cnt);
+        word = next_word;
     }
 
     // ---- lane l holds rows 4*(l/16) .. +3 of right-hand side l%16
@@ -457,15 +357,27 @@ __global__ __launch_bounds__(256) void endor_gemm_zero_kernel(float *__restrict_
     if (i < count) y[i] = 0.0f;
 }
 
-// column ranges per row group: enough waves to fill the chip, never more than kMaxSplit
+// Column ranges per row group.  The chip holds kResident workgroups at a time (five per compute
+// unit, by registers and LDS), so the launch runs in ceil(workgroups / kResident) waves of
+// workgroups, each as long as one workgroup: its rounds plus a start-up worth about two.  Pick
+// the split that minimises the product (measured on 28672 x 8192: 4 ranges 98 us, 6 ranges,
+// which spill into a third wave, 111 us), the smaller one on a tie.
+constexpr int64_t kResident = 256 * 5;
 uint32_t choose_split(int64_t rows, int64_t cols) {
     const int64_t groups = (rows + kRows - 1) / kRows;
+    const int64_t wgs = (groups + kGemmWaves - 1) / kGemmWaves;
     const int64_t segs = (cols + kSegCols - 1) / kSegCols;
-    int64_t k = (6144 + groups - 1) / groups;  // about 24 waves per compute unit
-    if (k > kMaxSplit) k = kMaxSplit;
-    if (k > segs) k = segs;
-    if (k < 1) k = 1;
-    return static_cast<uint32_t>(k);
+    int64_t best = 1, best_cost = -1;
+    for (int64_t k = 1; k <= kMaxSplit && k <= segs; ++k) {
+        const int64_t per = (segs + k - 1) / k;
+        if ((k - 1) * per >= segs) continue;  // the last range would be empty
+        const int64_t cost = ((wgs * k + kResident - 1) / kResident) * (per + 2);
+        if (best_cost < 0 || cost < best_cost) {
+            best = k;
+            best_cost = cost;
+        }
+    }
+    return static_cast<uint32_t>(best);
 }
 
 }  // namespace
@@ -524,7 +436,8 @@ extern "C" endor_status endor_gemm_f16(int64_t rows, int64_t cols, const uint8_t
     G.segs_per_split = static_cast<uint32_t>((segs + ksplit - 1) / ksplit);
     G.x_fast = ((reinterpret_cast<uintptr_t>(d_x) & 15) == 0 && (ldx * 2) % 16 == 0) ? 1u : 0u;
     const int64_t groups = (rows + kRows - 1) / kRows;
-    hipLaunchKernelGGL(endor_gemm_f16_kernel, dim3(static_cast<unsigned>(groups * ksplit)), dim3(64), 0, s, G);
+    const int64_t blocks = (groups + kGemmWaves - 1) / kGemmWaves * ksplit;
+    hipLaunchKernelGGL(endor_gemm_f16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * kGemmWaves), 0, s, G);
     if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
     if (ksplit > 1) {
         hipLaunchKernelGGL(endor_gemm_reduce_kernel, dim3(static_cast<unsigned>((count + 255) / 256)), dim3(256), 0, s,

@@ -45,6 +45,7 @@ namespace {
 
 using endor_device::chunk_base;
 using endor_device::dpp_or_zero;
+using endor_device::load_to_lds16;
 using endor_device::load_window16;
 using endor_device::place_window;
 using endor_device::window_tables_init;
@@ -52,6 +53,7 @@ using endor_device::WindowTables;
 using endor_device::row_inclusive_scan;
 using endor_device::u32x4;
 using endor_device::wave_inclusive_scan;
+using endor_device::wait_loads_to_lds;
 using endor_device::wave_sum;
 
 using endor_layout::kTileElems;      // flat positions per tile
@@ -215,17 +217,6 @@ struct alignas(16) WaveScratch {
     uint64_t words[kTileWords];  // the tile's bitmap words
     uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
 };
-
-// 16 bytes per lane from global memory straight into LDS: lane l writes lds_base + 16*l
-// (lds_base is wave-uniform; lanes that are switched off write nothing).  kStreamed marks the
-// load non-temporal.
-template <bool kStreamed = true>
-__device__ __forceinline__ void load_to_lds16(const u32x4 *src, u32x4 *lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, kStreamed ? 2 : 0);
-}
-// Every load this wave has issued is complete, those into LDS included (s_waitcnt vmcnt(0)).
-__device__ __forceinline__ void wait_loads_to_lds() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
 template <int E>
