@@ -688,7 +688,6 @@ __device__ __forceinline__ float wave_sum_f32(float x) {
 // one fused multiply-add with fp16 operands widened in the instruction (v_fma_mix_f32), so
 // fp16 subnormals count in full (the packed dot-product instructions flush them).
 struct GemvSink {
-    u32x4 xs[8];  // x[le .. le+7] for each step of the current segment
     float acc;
     __device__ __forceinline__ void pair(uint32_t w2, uint32_t x2) {
 #pragma clang fp contract(off)  // keep the two multiply-adds apart: fused into a dot product they would flush
@@ -697,11 +696,12 @@ struct GemvSink {
         acc = __builtin_fmaf(static_cast<float>(w.x), static_cast<float>(x.x), acc);
         acc = __builtin_fmaf(static_cast<float>(w.y), static_cast<float>(x.y), acc);
     }
-    __device__ __forceinline__ void operator()(int k, uint32_t, u32x4 d) {
-        pair(d.x, xs[k].x);
-        pair(d.y, xs[k].y);
-        pair(d.z, xs[k].z);
-        pair(d.w, xs[k].w);
+    // 8 expanded elements against the matching 8 entries of x
+    __device__ __forceinline__ void operator()(u32x4 d, u32x4 x) {
+        pair(d.x, x.x);
+        pair(d.y, x.y);
+        pair(d.z, x.z);
+        pair(d.w, x.w);
     }
 };
 
@@ -723,45 +723,89 @@ struct GemvParams {
 // Elements whose bit is 0 enter as +0.0, as they would from the dense matrix.  The next
 // segment's bitmap word is loaded before the current one is worked on.
 // (Measured alternatives on 28672 x 8192, half kept: values staged in LDS and gathered element
-// by element 83 us, staged and read as windows 76 us, this form 72 us; a wave taking four rows
-// in turn 143 us: a wave's segments run one after the other, so what counts is the number of
-// independent waves.  Counters of this form: the vector cache handles some 530 line accesses
-// per segment where 200 would do if no two lanes shared a line.)
+// by element 83 us, staged and read as windows 76 us, windows straight from memory 72 us, and
+// with x shared through LDS as below 64-67 us; a wave taking four rows in turn 143 us: a wave's
+// segments run one after the other, so what counts is the number of independent waves.  Counters
+// of the 72 us form: the vector cache handles some 530 line accesses per segment, 128 of them
+// for x, where 200 would do if no two lanes shared a line.)
 constexpr int kGemvSeg = 4096;  // columns a wave expands at a time
 
-// kFastX: x is 16-byte aligned and cols a multiple of 8, so every lane's 8 entries of x are one
-// aligned load (the general path, with its 8 guarded loads per step, lives in an instantiation of
-// its own because it costs some 60 registers).
+// kFastX: x is 16-byte aligned and cols a multiple of 8, so x moves in whole aligned 16-byte
+// pieces (the general path builds each piece from 8 guarded loads).
+//
+// The kGemvWaves rows of a workgroup walk their segments in step, so the segment's 4096 entries
+// of x are brought to LDS once per workgroup (one 16-byte piece per thread, straight from
+// memory into LDS on the fast path, double buffered, one barrier per segment) instead of once
+// per row: x is the same 8 KB for every row, and fetching it per row cost a quarter of the
+// vector cache's accesses.
+constexpr int kGemvWaves = 8;
+constexpr int kGemvXRounds = (kGemvSeg / 8 + 64 * kGemvWaves - 1) / (64 * kGemvWaves);  // 16-byte pieces of x per thread and segment
+
 template <bool kFastX>
-__global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
+__global__ __launch_bounds__(64 * kGemvWaves) void endor_gemv_f16_kernel(GemvParams G) {
     __shared__ WindowTables s_tables;
-    __shared__ uint32_t s_entry[kWaves][kGemvSeg / 8];
-    window_tables_init(s_tables, threadIdx.x);
-    __syncthreads();
+    __shared__ uint32_t s_entry[kGemvWaves][kGemvSeg / 8];
+    __shared__ u32x4 s_x[2][kGemvSeg / 8];
+    window_tables_init(s_tables, threadIdx.x);  // visible after the first segment's barrier
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
-    const int64_t i = int64_t(blockIdx.x) * kWaves + wave;
-    if (i >= G.rows) return;  // whole wave; no workgroup barrier follows
+    const int64_t i = int64_t(blockIdx.x) * kGemvWaves + wave;
+    const bool row_ok = i < G.rows;  // a wave past the last row still helps loading x
     uint32_t *entry = s_entry[wave];
     const int64_t nwords = (G.rows * G.cols + 63) >> 6;
-    const int64_t row_bit = i * G.cols;
+    const int64_t row_bit = (row_ok ? i : 0) * G.cols;
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(G.values);
     const uintptr_t vend = vbeg + 2 * static_cast<uintptr_t>(G.nnz);
-    uint64_t next_value = static_cast<uint64_t>(G.row_offsets[i]);
+    uint64_t next_value = row_ok ? static_cast<uint64_t>(G.row_offsets[i]) : 0;
     GemvSink sink;
     sink.acc = 0.0f;
-    uint64_t word = 0;
-    if (G.cols > 0)
-        word = segment_word(G.bitmap, nwords, row_bit, G.cols < kGemvSeg ? static_cast<uint32_t>(G.cols) : uint32_t(kGemvSeg), lane);
-    for (int64_t c0 = 0; c0 < G.cols; c0 += kGemvSeg) {
+
+    // this thread's piece of the segment of x that starts at column c0
+    auto load_x = [&](int64_t c0, uint32_t buf) {
+#pragma unroll
+        for (int q = 0; q < kGemvXRounds; ++q) {
+            const uint32_t piece = q * 64 * kGemvWaves + threadIdx.x;
+            if (64 * kGemvWaves * kGemvXRounds > kGemvSeg / 8 && piece >= kGemvSeg / 8) break;  // more threads than pieces
+            const int64_t c = c0 + 8 * int64_t(piece);
+            if (kFastX) {
+                // past the row's end x reads as zero (the expanded elements there are zero, but
+                // zero times whatever LDS held could be NaN)
+                if (c < G.cols)
+                    load_to_lds16<false>(reinterpret_cast<const u32x4 *>(G.x + c), &s_x[buf][q * 64 * kGemvWaves + 64 * wave]);
+                else
+                    s_x[buf][piece] = u32x4{0u, 0u, 0u, 0u};
+            } else {
+                uint32_t h[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) h[j] = (c + j < G.cols) ? uint32_t(G.x[c + j]) : 0u;
+                u32x4 f;
+                f.x = h[0] | (h[1] << 16);
+                f.y = h[2] | (h[3] << 16);
+                f.z = h[4] | (h[5] << 16);
+                f.w = h[6] | (h[7] << 16);
+                s_x[buf][piece] = f;
+            }
+        }
+    };
+    auto row_word = [&](int64_t c0) -> uint64_t {
+        const int64_t left = G.cols - c0;
+        if (!row_ok || left <= 0) return 0;
+        return segment_word(G.bitmap, nwords, row_bit + c0, left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg),
+                            lane);
+    };
+
+    if (G.cols > 0) load_x(0, 0);
+    uint64_t word = row_word(0);
+    uint32_t buf = 0;
+    for (int64_t c0 = 0; c0 < G.cols; c0 += kGemvSeg, buf ^= 1u) {
         const int64_t left = G.cols - c0;
         const uint32_t nbits = left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg);
-        uint64_t next_word = 0;
-        if (left > kGemvSeg) {
-            const int64_t l2 = left - kGemvSeg;
-            next_word = segment_word(G.bitmap, nwords, row_bit + c0 + kGemvSeg,
-                                     l2 < kGemvSeg ? static_cast<uint32_t>(l2) : uint32_t(kGemvSeg), lane);
-        }
+        // this thread's piece of the segment's x has landed; after the barrier all of them have,
+        // and every wave is through the previous segment (whose x the next load overwrites)
+        wait_loads_to_lds();
+        __syncthreads();
+        if (left > kGemvSeg) load_x(c0 + kGemvSeg, buf ^ 1u);
+        const uint64_t next_word = row_word(c0 + kGemvSeg);
         const uint32_t pc = __popcll(word);
         const uint32_t incl = wave_inclusive_scan(pc);
         const uint32_t cnt = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
@@ -786,24 +830,6 @@ __global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
             reinterpret_cast<u32x4 *>(entry)[2 * lane] = lo;
             reinterpret_cast<u32x4 *>(entry)[2 * lane + 1] = hi;
         }
-#pragma unroll
-        for (int k = 0; k < kGemvSeg / 512; ++k) {
-            const uint32_t le = (k * 64 + lane) * 8;
-            if (kFastX) {
-                u32x4 f;
-                f.x = f.y = f.z = f.w = 0;
-                if (le < nbits) f = *reinterpret_cast<const u32x4 *>(G.x + c0 + le);
-                sink.xs[k] = f;
-            } else {
-                uint32_t h[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) h[j] = (le + j < nbits) ? uint32_t(G.x[c0 + le + j]) : 0u;
-                sink.xs[k].x = h[0] | (h[1] << 16);
-                sink.xs[k].y = h[2] | (h[3] << 16);
-                sink.xs[k].z = h[4] | (h[5] << 16);
-                sink.xs[k].w = h[6] | (h[7] << 16);
-            }
-        }
         wave_lds_sync();
         const uintptr_t vseg = vbeg + 2 * next_value;
         uint32_t e[kGemvSeg / 512];
@@ -816,14 +842,14 @@ __global__ __launch_bounds__(kBlock) void endor_gemv_f16_kernel(GemvParams G) {
 #pragma unroll
         for (int k = 0; k < kGemvSeg / 512; ++k) {
             const u32x4 d = place_window(s_tables, e[k] & 0xffu, win[k]);
-            sink(k, 0, d);
+            sink(d, s_x[buf][k * 64 + lane]);
         }
         wave_lds_sync();  // the next segment's entries stay behind this segment's reads
         next_value += cnt;
         word = next_word;
     }
     const float total = wave_sum_f32(sink.acc);
-    if (lane == 0) G.y[i] = total;
+    if (lane == 0 && row_ok) G.y[i] = total;
 }
 
 // ---------------------------------------------------------------- device-side compression
@@ -1542,11 +1568,11 @@ extern "C" endor_status endor_gemv_f16(int64_t rows, int64_t cols, const uint8_t
     G.rows = rows;
     G.cols = cols;
     G.nnz = nnz;
-    const dim3 grid(static_cast<unsigned>((rows + kWaves - 1) / kWaves));
+    const dim3 grid(static_cast<unsigned>((rows + kGemvWaves - 1) / kGemvWaves)), block(64 * kGemvWaves);
     if ((reinterpret_cast<uintptr_t>(d_x) & 15) == 0 && cols % 8 == 0)
-        hipLaunchKernelGGL(endor_gemv_f16_kernel<true>, grid, dim3(kBlock), 0, static_cast<hipStream_t>(stream), G);
+        hipLaunchKernelGGL(endor_gemv_f16_kernel<true>, grid, block, 0, static_cast<hipStream_t>(stream), G);
     else
-        hipLaunchKernelGGL(endor_gemv_f16_kernel<false>, grid, dim3(kBlock), 0, static_cast<hipStream_t>(stream), G);
+        hipLaunchKernelGGL(endor_gemv_f16_kernel<false>, grid, block, 0, static_cast<hipStream_t>(stream), G);
     if (hipGetLastError() != hipSuccess) return ENDOR_ERR_HIP;
     return ENDOR_OK;
 }
