@@ -130,24 +130,49 @@ __device__ __forceinline__ u32x4 place_window(const WindowTables &T, uint32_t bi
     return d;
 }
 
-// The 16 bytes (8 values of 16 bits) at byte address p, which is 2-byte aligned only; bytes
-// outside [vbeg, vend) read as 0.  Read as the 20 bytes from the dword boundary below p and
-// shifted into place: a load whose address is not a multiple of 4 costs the cache nearly
-// twice the accesses (measured).  Normal cached loads: the windows overlap.
+// The 16 bytes (8 values of 16 bits) at byte address p, which is 2-byte aligned only.  Read as
+// the 20 bytes from the dword boundary below p and shifted into place: a load whose address
+// is not a multiple of 4 costs the cache nearly twice the accesses (measured).  Normal cached
+// loads: the windows overlap.
+//
+// In two halves, so that a caller issues the loads of all its windows before it uses the
+// first; the caller guarantees that the 20 bytes lie inside the array.  (With the load under a
+// per-lane bounds test the compiler puts a full wait behind every one of them, and a wave's
+// eight windows became eight trips to memory, one after the other; so the callers test a whole
+// segment at once, wave-uniformly, and send the few segments at the very ends of the array
+// through window_guarded in a loop of their own.)
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
-__device__ __forceinline__ u32x4 load_window16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
-    const uintptr_t a4 = p & ~uintptr_t(3);
-    if (a4 >= vbeg && a4 + 20 <= vend) {
-        const u32x4 d = *reinterpret_cast<const u32x4_a4 *>(a4);
-        const uint32_t sh = static_cast<uint32_t>(p) & 3u;  // 0 or 2
-        const uint32_t d4 = *reinterpret_cast<const uint32_t *>(a4 + 16);  // the last value of a shifted window
-        u32x4 w;
-        w.x = __builtin_amdgcn_alignbyte(d.y, d.x, sh);
-        w.y = __builtin_amdgcn_alignbyte(d.z, d.y, sh);
-        w.z = __builtin_amdgcn_alignbyte(d.w, d.z, sh);
-        w.w = __builtin_amdgcn_alignbyte(d4, d.w, sh);
-        return w;
-    }
+
+struct WindowLoad {
+    u32x4 d;      // the four dwords from the dword boundary at or below p
+    uint32_t d4;  // the fifth: the last value of a shifted window
+};
+
+// true when every window that starts in [first, last] can be read with window_issue
+__device__ __forceinline__ bool windows_inside(uintptr_t first, uintptr_t last, uintptr_t vbeg, uintptr_t vend) {
+    return (first & ~uintptr_t(3)) >= vbeg && last + 20 <= vend;
+}
+
+__device__ __forceinline__ WindowLoad window_issue(uintptr_t p) {
+    const uintptr_t a = p & ~uintptr_t(3);
+    WindowLoad L;
+    L.d = *reinterpret_cast<const u32x4_a4 *>(a);
+    L.d4 = *reinterpret_cast<const uint32_t *>(a + 16);
+    return L;
+}
+
+__device__ __forceinline__ u32x4 window_finish(const WindowLoad &L, uintptr_t p) {
+    const uint32_t sh = static_cast<uint32_t>(p) & 3u;  // 0 or 2
+    u32x4 w;
+    w.x = __builtin_amdgcn_alignbyte(L.d.y, L.d.x, sh);
+    w.y = __builtin_amdgcn_alignbyte(L.d.z, L.d.y, sh);
+    w.z = __builtin_amdgcn_alignbyte(L.d.w, L.d.z, sh);
+    w.w = __builtin_amdgcn_alignbyte(L.d4, L.d.w, sh);
+    return w;
+}
+
+// The same window element by element, with bytes outside [vbeg, vend) read as 0.
+__device__ __forceinline__ u32x4 window_guarded(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
     uint32_t d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -156,12 +181,12 @@ __device__ __forceinline__ u32x4 load_window16(uintptr_t p, uintptr_t vbeg, uint
         if (q >= vbeg && q + 2 <= vend) v = *reinterpret_cast<const uint16_t *>(q);
         d[j >> 1] |= v << (16 * (j & 1));
     }
-    u32x4 r;
-    r.x = d[0];
-    r.y = d[1];
-    r.z = d[2];
-    r.w = d[3];
-    return r;
+    u32x4 w;
+    w.x = d[0];
+    w.y = d[1];
+    w.z = d[2];
+    w.w = d[3];
+    return w;
 }
 
 }  // namespace endor_device

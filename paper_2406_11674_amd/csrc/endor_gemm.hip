@@ -52,7 +52,11 @@ namespace {
 
 using endor_device::chunk_base;
 using endor_device::load_to_lds16;
-using endor_device::load_window16;
+using endor_device::window_finish;
+using endor_device::window_guarded;
+using endor_device::window_issue;
+using endor_device::WindowLoad;
+using endor_device::windows_inside;
 using endor_device::place_window;
 using endor_device::window_tables_init;
 using endor_device::WindowTables;
@@ -303,27 +307,39 @@ __global__ __launch_bounds__(64 * kGemmWaves) void endor_gemm_f16_kernel(GemmPar
 
         // ---- loads: the next segment's bitmap word, this segment's windows
         const uint64_t next_word = seg + 1 < seg_end ? load_word(seg + 1) : 0;
-        uint32_t entry[kSteps];
-        u32x4 win[kSteps];
-#pragma unroll
-        for (int t = 0; t < kSteps; ++t) entry[t] = info[lr][t * 4 + lj];
-#pragma unroll
-        for (int t = 0; t < kSteps; ++t) win[t] = load_window16(cursor + 2 * uintptr_t(entry[t] >> 8), vbeg, vend);
-
-        // ---- 8 steps: place the values of 8 elements of row lr, hand them to the multiplying lane, multiply
-#pragma unroll
-        for (int t = 0; t < kSteps; ++t) {
-            const u32x4 e = place_window(S.tables, entry[t] & 0xffu, win[t]);
+        const uint8_t *xt = &S.xt[buf][mr][16 * mq];  // right-hand side mr, column block mq of step 0
+        // one step's expanded 16 bytes of row lr go to the lane that multiplies them
+        auto step = [&](int t, u32x4 e) {
             u32x4 a;
             a.x = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.x)));
             a.y = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.y)));
             a.z = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.z)));
             a.w = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from_lane, static_cast<int>(e.w)));
-            u32x4 xb;  // 8 columns of right-hand side mr (rows of the tile at or past nb hold nothing)
-            xb.x = xb.y = xb.z = xb.w = 0;
-            if (x_ok) xb = *reinterpret_cast<const u32x4 *>(&S.xt[buf][mr][64 * t + 16 * mq]);
+            const u32x4 xb = *reinterpret_cast<const u32x4 *>(xt + 64 * t);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, xb), acc, 0,
                                                          0, 0);
+        };
+        // every window of this round starts in [cursor, cursor + 2 cnt] of its row; all rows' windows
+        // lie inside `values` except in the rounds at the very ends of the array
+        const bool row_inside = windows_inside(cursor, cursor + 2 * uintptr_t(cnt), vbeg, vend);
+        if (__builtin_amdgcn_ballot_w64(!row_inside) == 0) {  // wave-uniform
+            uint32_t entry[kSteps];
+            WindowLoad win[kSteps];
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) entry[t] = info[lr][t * 4 + lj];
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) win[t] = window_issue(cursor + 2 * uintptr_t(entry[t] >> 8));
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t)
+                step(t, place_window(S.tables, entry[t] & 0xffu,
+                                     window_finish(win[t], cursor + 2 * uintptr_t(entry[t] >> 8))));
+        } else {
+#pragma unroll 1
+            for (int t = 0; t < kSteps; ++t) {
+                const uint32_t entry = info[lr][t * 4 + lj];
+                step(t, place_window(S.tables, entry & 0xffu,
+                                     window_guarded(cursor + 2 * uintptr_t(entry >> 8), vbeg, vend)));
+            }
         }
         // the next round's LDS writes must stay behind this round's LDS reads
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

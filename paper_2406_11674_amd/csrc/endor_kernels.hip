@@ -46,7 +46,11 @@ namespace {
 using endor_device::chunk_base;
 using endor_device::dpp_or_zero;
 using endor_device::load_to_lds16;
-using endor_device::load_window16;
+using endor_device::window_finish;
+using endor_device::window_guarded;
+using endor_device::window_issue;
+using endor_device::WindowLoad;
+using endor_device::windows_inside;
 using endor_device::place_window;
 using endor_device::window_tables_init;
 using endor_device::WindowTables;
@@ -832,17 +836,25 @@ __global__ __launch_bounds__(64 * kGemvWaves) void endor_gemv_f16_kernel(GemvPar
         }
         wave_lds_sync();
         const uintptr_t vseg = vbeg + 2 * next_value;
-        uint32_t e[kGemvSeg / 512];
-        u32x4 win[kGemvSeg / 512];
+        if (windows_inside(vseg, vseg + 2 * uintptr_t(cnt), vbeg, vend)) {  // wave-uniform
+            uint32_t e[kGemvSeg / 512];
+            WindowLoad win[kGemvSeg / 512];
 #pragma unroll
-        for (int k = 0; k < kGemvSeg / 512; ++k) e[k] = entry[k * 64 + lane];
+            for (int k = 0; k < kGemvSeg / 512; ++k) e[k] = entry[k * 64 + lane];
 #pragma unroll
-        for (int k = 0; k < kGemvSeg / 512; ++k)
-            win[k] = load_window16(vseg + 2 * uintptr_t(e[k] >> 8), vbeg, vend);
+            for (int k = 0; k < kGemvSeg / 512; ++k) win[k] = window_issue(vseg + 2 * uintptr_t(e[k] >> 8));
 #pragma unroll
-        for (int k = 0; k < kGemvSeg / 512; ++k) {
-            const u32x4 d = place_window(s_tables, e[k] & 0xffu, win[k]);
-            sink(d, s_x[buf][k * 64 + lane]);
+            for (int k = 0; k < kGemvSeg / 512; ++k) {
+                const u32x4 w = window_finish(win[k], vseg + 2 * uintptr_t(e[k] >> 8));
+                sink(place_window(s_tables, e[k] & 0xffu, w), s_x[buf][k * 64 + lane]);
+            }
+        } else {  // a segment at the very beginning or end of `values`
+#pragma unroll 1
+            for (int k = 0; k < kGemvSeg / 512; ++k) {
+                const uint32_t e = entry[k * 64 + lane];
+                const u32x4 w = window_guarded(vseg + 2 * uintptr_t(e >> 8), vbeg, vend);
+                sink(place_window(s_tables, e & 0xffu, w), s_x[buf][k * 64 + lane]);
+            }
         }
         wave_lds_sync();  // the next segment's entries stay behind this segment's reads
         next_value += cnt;
