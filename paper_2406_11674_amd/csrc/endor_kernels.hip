@@ -358,6 +358,26 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
                                             uint32_t cnt, uintptr_t vbeg, uintptr_t vend, Sink &sink) {
     using Sh = Shape<E>;
     using WS = WaveScratch<E, kCap>;
+    // --- the loads of the tile's value slice (16-byte units from the 16-byte boundary at or
+    //     below its first value) go out first: they depend on the table only, and the wave's
+    //     bitmap word, loaded by the caller, may still be on its way
+    const uintptr_t a16 = vaddr & ~uintptr_t(15);
+    const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
+    cnt = cnt > kCap ? kCap : cnt;  // a stale or foreign table must not overrun the staging area
+    const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
+    // the whole slice lies inside `values`: all tiles but the first and last of an array that
+    // does not begin and end on 16-byte boundaries
+    const bool direct = nch != 0 && a16 >= vbeg && a16 + 16 * uintptr_t(nch) <= vend;
+    if (direct) {
+        // Straight from memory into the staging area (global_load_lds_dwordx4: lane l of an
+        // instruction deposits its 16 bytes at the LDS address in M0 plus 16*l), no registers
+        // in between.  Values are read once: streamed past the caches.
+#pragma unroll
+        for (int q = 0; q < WS::kStageRounds; ++q) {
+            const uint32_t ch = q * 64 + lane;
+            if (ch < nch) load_to_lds16(reinterpret_cast<const u32x4 *>(a16) + ch, &S.stage[q * 64]);
+        }
+    }
     const uint32_t pc = __popcll(word);
     const uint32_t incl = wave_inclusive_scan(pc);
     const uint32_t excl = incl - pc;
@@ -366,6 +386,7 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
         // table): stage and expand the tile one step at a time; a step has at most 1024 values
         const uint32_t ones = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
         if (ones > kCap) {  // wave-uniform
+            if (direct) wait_loads_to_lds();  // what is on its way into the staging area lands before it is reused
             S.words[lane] = word;
 #pragma unroll Sink::kStepUnroll
             for (int k = 0; k < Sh::kSteps; ++k) {
@@ -375,13 +396,13 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
                 const uint32_t last = static_cast<uint32_t>(
                     __builtin_amdgcn_ds_bpermute(4 * (w0 + Sh::kLaneElems - 1), static_cast<int>(incl)));
                 const uintptr_t va = vaddr + uintptr_t(E) * first;
-                const uintptr_t a16 = va & ~uintptr_t(15);
-                const uint32_t shift = static_cast<uint32_t>(va - a16) / E;
+                const uintptr_t b16 = va & ~uintptr_t(15);
+                const uint32_t sh = static_cast<uint32_t>(va - b16) / E;
                 const uint32_t n = last - first;  // <= 1024 <= kCap
-                const uint32_t nch = n ? (((shift + n) * E + 15) >> 4) : 0;
-                S.start[lane] = excl - first + shift;  // meaningful for the step's words only
-                for (uint32_t ch = lane; ch < nch; ch += 64)
-                    S.stage[ch] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
+                const uint32_t nc = n ? (((sh + n) * E + 15) >> 4) : 0;
+                S.start[lane] = excl - first + sh;  // meaningful for the step's words only
+                for (uint32_t ch = lane; ch < nc; ch += 64)
+                    S.stage[ch] = load_values16<E>(b16 + 16 * uintptr_t(ch), vbeg, vend);
                 wave_lds_sync();
                 expand_step<E, kCap>(S, k, lane, sink);
                 wave_lds_sync();
@@ -389,27 +410,11 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
             return;
         }
     }
-    // --- issue the loads of the tile's value slice (16-byte units from the 16-byte
-    //     boundary at or below its first value)
-    const uintptr_t a16 = vaddr & ~uintptr_t(15);
-    const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
-    cnt = cnt > kCap ? kCap : cnt;  // a stale or foreign table must not overrun the staging area
-    const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
-    if (nch != 0 && a16 >= vbeg && a16 + 16 * uintptr_t(nch) <= vend) {  // the whole slice lies inside `values`
-        // Straight from memory into the staging area (global_load_lds_dwordx4: lane l of an
-        // instruction deposits its 16 bytes at the LDS address in M0 plus 16*l), no registers
-        // in between.  Values are read once: streamed past the caches.
-        S.words[lane] = word;
-        S.start[lane] = excl + shift;
-#pragma unroll
-        for (int q = 0; q < WS::kStageRounds; ++q) {
-            const uint32_t ch = q * 64 + lane;
-            if (ch < nch) load_to_lds16(reinterpret_cast<const u32x4 *>(a16) + ch, &S.stage[q * 64]);
-        }
+    S.words[lane] = word;
+    S.start[lane] = excl + shift;
+    if (direct) {
         wait_loads_to_lds();
-    } else {  // the first or last tile of an array that does not begin and end on 16-byte boundaries
-        S.words[lane] = word;
-        S.start[lane] = excl + shift;
+    } else {
 #pragma unroll 1
         for (uint32_t ch = lane; ch < nch; ch += 64)
             S.stage[ch] = load_values16<E>(a16 + 16 * uintptr_t(ch), vbeg, vend);
@@ -441,11 +446,12 @@ __global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
     const uint32_t tail_bits = static_cast<uint32_t>(n & 63);
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(M.values);
     const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(M.nnz);
+    // the bitmap word first: its load is in flight while the table is looked up
+    const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
     const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl;
     const uint64_t base = chunk_base(M.chunk_total, c, lane);
     const uint32_t o0 = tile_off[0];
     const uint32_t cnt = tile_off[1] - o0;  // 1 bits in this tile
-    const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
     const int64_t e0 = tile * kTileElems;
     const int64_t left = n - e0;
     StoreSink<E, kAlignedOut, kBurst> sink;
