@@ -894,6 +894,24 @@ __device__ __forceinline__ u32x4 load_dense16(const uint8_t *tile_in, uint32_t l
     return r;
 }
 
+// A lane's kSteps 16-byte pieces of a tile of the dense matrix.  A whole, aligned tile is one
+// wave-uniform case with unconditional loads, all issued before the first is used (under a
+// per-piece bounds test the compiler waits after every load); only the ragged last tile and
+// unaligned inputs go piece by piece.
+template <int E, bool kAlignedIn>
+__device__ __forceinline__ void load_dense_tile(const uint8_t *tile_in, uint32_t lane, uint32_t nvalid,
+                                                u32x4 (&d)[Shape<E>::kSteps]) {
+    using Sh = Shape<E>;
+    if (kAlignedIn && nvalid == kTileElems) {
+#pragma unroll
+        for (int k = 0; k < Sh::kSteps; ++k)
+            d[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(tile_in) + k * 64 + lane);
+    } else {
+#pragma unroll
+        for (int k = 0; k < Sh::kSteps; ++k) d[k] = load_dense16<E, kAlignedIn>(tile_in, (k * 64 + lane) * Sh::kLaneElems, nvalid);
+    }
+}
+
 // bit j = (element j of the 16 bytes is not the all-zero pattern)
 template <int E>
 __device__ __forceinline__ uint32_t nonzero_bits(u32x4 d) {
@@ -929,8 +947,7 @@ __global__ __launch_bounds__(64) void endor_mask_kernel(CompressParams C) {
     const uint32_t nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
     const uint8_t *tile_in = reinterpret_cast<const uint8_t *>(C.dense) + e0 * E;
     u32x4 d[Sh::kSteps];
-#pragma unroll
-    for (int k = 0; k < Sh::kSteps; ++k) d[k] = load_dense16<E, kAlignedIn>(tile_in, (k * 64 + lane) * Sh::kLaneElems, nvalid);
+    load_dense_tile<E, kAlignedIn>(tile_in, lane, nvalid, d);
 #pragma unroll
     for (int k = 0; k < Sh::kSteps; ++k) {
         const uint32_t bits = nonzero_bits<E>(d[k]);
@@ -956,6 +973,14 @@ __global__ __launch_bounds__(64) void endor_pack_kernel(CompressParams C) {
     __shared__ WaveScratch<E> S;
     const uint32_t lane = threadIdx.x;
     const int64_t tile = blockIdx.x;
+    // the tile's elements first: their loads are in flight while the table is looked up
+    const int64_t e0 = tile * kTileElems;
+    const int64_t left = C.n - e0;
+    const uint32_t nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
+    const uint8_t *tile_in = reinterpret_cast<const uint8_t *>(C.dense) + e0 * E;
+    u32x4 d[Sh::kSteps];
+    load_dense_tile<E, kAlignedIn>(tile_in, lane, nvalid, d);
+
     const MatParams &M = C.table;
     const uint32_t c = static_cast<uint32_t>(tile / kTilesPerChunk);
     const uint32_t tl = static_cast<uint32_t>(tile % kTilesPerChunk);
@@ -964,14 +989,6 @@ __global__ __launch_bounds__(64) void endor_pack_kernel(CompressParams C) {
     uint32_t cnt = tile_off[1] - o0;
     cnt = cnt > kTileElems ? kTileElems : cnt;
     const uint64_t first = chunk_base(M.chunk_total, c, lane) + o0;  // index of the tile's first value
-
-    const int64_t e0 = tile * kTileElems;
-    const int64_t left = C.n - e0;
-    const uint32_t nvalid = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
-    const uint8_t *tile_in = reinterpret_cast<const uint8_t *>(C.dense) + e0 * E;
-    u32x4 d[Sh::kSteps];
-#pragma unroll
-    for (int k = 0; k < Sh::kSteps; ++k) d[k] = load_dense16<E, kAlignedIn>(tile_in, (k * 64 + lane) * Sh::kLaneElems, nvalid);
 
     const uintptr_t vbase = reinterpret_cast<uintptr_t>(C.values);
     const uintptr_t vaddr = vbase + E * first;
