@@ -642,24 +642,24 @@ __global__ __launch_bounds__(kBlock) void endor_gather_cols_kernel(ColsParams C)
             cn[u] = q < C.nsel ? C.sel[q] : -1;
         }
         uint32_t v[kQ];
-        bool live[kQ];
+        bool live[kQ], hit[kQ];
 #pragma unroll
         for (int u = 0; u < kQ; ++u) {
             // an index outside the matrix (or past nsel) leaves its output column untouched
             live[u] = static_cast<uint64_t>(c[u]) < ucols;
-            v[u] = 0;
-            if (live[u]) {
-                const uint32_t cc = static_cast<uint32_t>(c[u]);
-                const uint32_t piece = s_piece[cc >> 5];
-                const uint32_t b = cc & 31;
-                if ((piece >> b) & 1) {
-                    const uint32_t r = s_before[cc >> 5] + __popc(piece & ((1u << b) - 1));  // rank inside the row
-                    if (r < room)
-                        v[u] = (E == 2) ? uint32_t(reinterpret_cast<const uint16_t *>(row_values)[r])
-                                        : uint32_t(row_values[r]);
-                }
-            }
+            const uint32_t cc = live[u] ? static_cast<uint32_t>(c[u]) : 0u;
+            const uint32_t piece = s_piece[cc >> 5];
+            const uint32_t b = cc & 31;
+            const uint32_t r = s_before[cc >> 5] + __popc(piece & ((1u << b) - 1));  // rank inside the row
+            hit[u] = live[u] && ((piece >> b) & 1) != 0 && r < room;
+            // The load itself is unconditional (a query without a value reads the first selected
+            // index instead and drops it): with the load under the test, the compiler waits for
+            // memory after every query and every store, one at a time.
+            const uint8_t *at = hit[u] ? row_values + size_t(E) * r : reinterpret_cast<const uint8_t *>(C.sel);
+            v[u] = (E == 2) ? uint32_t(*reinterpret_cast<const uint16_t *>(at)) : uint32_t(*at);
         }
+#pragma unroll
+        for (int u = 0; u < kQ; ++u) v[u] = hit[u] ? v[u] : 0u;
 #pragma unroll
         for (int u = 0; u < kQ; ++u) {
             const int64_t q = q0 + u * kBlock + threadIdx.x;
