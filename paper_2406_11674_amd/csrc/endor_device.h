@@ -46,7 +46,18 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
 __device__ __forceinline__ uint64_t chunk_base(const uint32_t *chunk_total, uint32_t c, uint32_t lane) {
     if (c == 0) return 0;
     uint32_t part = 0;
-    for (uint32_t j = lane; j < c; j += 64) part += chunk_total[j];
+    // 256 totals per pass, the four loads of a lane issued together (an index past the end reads
+    // the last total again and drops it: a load under a test is waited for on the spot)
+    for (uint32_t j0 = 0; j0 < c; j0 += 256) {
+        uint32_t t[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t j = j0 + 64 * k + lane;
+            t[k] = chunk_total[j < c ? j : c - 1];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) part += (j0 + 64 * k + lane < c) ? t[k] : 0u;
+    }
     const uint32_t lo = wave_sum(part & 0xffffu);
     const uint32_t hi = wave_sum(part >> 16);
     return uint64_t(lo) + (uint64_t(hi) << 16);
