@@ -28,8 +28,10 @@
 // four lanes of a quad read neighbouring windows of one row, and the expanded 16 bytes are
 // handed to the multiplying lane with ds_bpermute.  (An earlier form staged every row's slice
 // in LDS and gathered the values one by one: 126 / 138 us for 1 / 16 right-hand sides on
-// 28672 x 8192, bound by LDS; this one takes 98 / 122 us, bound by the rate at which the
-// vector cache accepts line accesses.)
+// 28672 x 8192, bound by LDS; this one takes 91 / 101 us, bound by the rate at which the
+// vector cache accepts line accesses.)  A round's eight window loads per lane go out back to
+// back behind one wave-uniform bounds test; the rounds at the very ends of `values` take a
+// rolled loop with guarded element-wise loads instead.
 // X: the four waves of a workgroup work on neighbouring row groups and the same column
 // range; the round's 256 columns of all right-hand sides are brought to LDS once per
 // workgroup (global_load_lds_dwordx4, double buffered, one barrier per round) and every wave

@@ -769,6 +769,32 @@ def test_gemm_unaligned_x_and_padded_rows_of_x():
     assert np.all(np.abs(Y2.cpu().numpy().astype(np.float64) - ref) <= tol)
 
 
+@pytest.mark.parametrize("voff", [1, 3, 6])
+@pytest.mark.parametrize("shape", [(50, 9001), (200, 4096), (33, 700)], ids=str)
+def test_products_with_values_at_2_byte_alignment(voff, shape):
+    """`values` starting 2, 6 or 12 bytes off a 16-byte boundary, with guard patterns around it:
+    the products read 20-byte windows from dword boundaries, and those at the two ends of the
+    array must take the guarded path."""
+    rows, cols = shape
+    _say(f"products, values offset {voff} elements, shape {shape}")
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=21 + voff)
+    c = endor.compress(w)
+    vbuf = torch.full((voff + c.nnz + 24,), 0x7E00, dtype=torch.int16, device="cuda")   # NaN patterns around
+    vbuf[voff:voff + c.nnz] = torch.from_numpy(c.values.view(np.int16)).cuda()
+    bm = torch.from_numpy(c.bitmap).cuda()
+    m = endor.DeviceMatrix(rows, cols, bm, vbuf[voff:voff + c.nnz], c.nnz)
+    ws, ro = endor.build_offsets(m, row_offsets=True)
+    x16 = np.random.default_rng(2).standard_normal(cols).astype(np.float16)
+    y = endor.gemv_f16(m, ro, torch.from_numpy(x16.view(np.int16)).cuda().view(torch.float16))
+    X16 = np.random.default_rng(3).standard_normal((3, cols)).astype(np.float16)
+    Y = endor.gemm_f16(m, ws, torch.from_numpy(X16.view(np.int16)).cuda().view(torch.float16))
+    torch.cuda.synchronize()
+    ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= _gemv_tolerance(w, x16, cols))
+    refm = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+    assert np.all(np.abs(Y.cpu().numpy().astype(np.float64) - refm) <= _gemm_tolerance(w, X16, cols))
+
+
 def test_gemm_nonfinite_x_like_the_dense_product():
     rows, cols = 4, 100
     w = synth.pruned_fp16(rows, cols, 0.5, seed=9)
