@@ -514,28 +514,43 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
     const int64_t left = R.cols - int64_t(g) * kTileElems;
     const uint32_t nbits = left < kTileElems ? static_cast<uint32_t>(left) : uint32_t(kTileElems);
 
+    // everything that depends on the row index only goes out together: the segment's own bits,
+    // the row's first value, and the bitmap words before the segment
+    const uint64_t word = segment_word(R.bitmap, nwords, e, nbits, lane);
+    const uint64_t row_first = static_cast<uint64_t>(R.row_offsets[i]);
+
     // 1 bits of the row before this segment: words [row_bit>>6, e>>6], first and last partial.
     // A lane's share stays below 2^28; the total may not fit 32 bits for very wide rows, so
-    // the two 16-bit halves are summed across the wave separately.
+    // the two 16-bit halves are summed across the wave separately.  Two words per lane and
+    // pass, loaded unconditionally (an index past the last word reads the last again and is
+    // dropped), so that a pass is one trip to memory.
     uint64_t before = 0;
     {
         uint32_t part = 0;
-        const int64_t wa = row_bit >> 6, wb = e >> 6;
-        for (int64_t w = wa + lane; w <= wb; w += 64) {
-            uint64_t x = w < nwords ? R.bitmap[w] : 0;
-            if (w == wa) x &= ~uint64_t(0) << (row_bit & 63);
-            if (w == wb) x &= (uint64_t(1) << (e & 63)) - 1;
-            part += __popcll(x);
+        const int64_t wa = row_bit >> 6, wb = e >> 6;  // wb < nwords: e is a position of the matrix
+        for (int64_t w0 = wa; w0 <= wb; w0 += 128) {
+            uint64_t x[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int64_t w = w0 + 64 * k + lane;
+                x[k] = R.bitmap[w <= wb ? w : wb];
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int64_t w = w0 + 64 * k + lane;
+                uint64_t y = w <= wb ? x[k] : 0;
+                if (w == wa) y &= ~uint64_t(0) << (row_bit & 63);
+                if (w == wb) y &= (uint64_t(1) << (e & 63)) - 1;
+                part += __popcll(y);
+            }
         }
         before = uint64_t(wave_sum(part & 0xffffu)) + (uint64_t(wave_sum(part >> 16)) << 16);
     }
-
-    const uint64_t word = segment_word(R.bitmap, nwords, e, nbits, lane);
     const uint32_t cnt = wave_sum(__popcll(word));
 
     const uintptr_t vbeg = reinterpret_cast<uintptr_t>(R.values);
     const uintptr_t vend = vbeg + E * static_cast<uintptr_t>(R.nnz);
-    const uint64_t first = static_cast<uint64_t>(R.row_offsets[i]) + before;
+    const uint64_t first = row_first + before;
     StoreSink<E, kAlignedOut, false> sink;
     sink.out = reinterpret_cast<uint8_t *>(R.out) + (r * R.cols + int64_t(g) * kTileElems) * E;
     sink.nvalid = nbits;
