@@ -15,18 +15,27 @@
 //      independent (no workgroup barrier; measured faster on MI355X than wider
 //      workgroups or several tiles per wave).  The wave adds up the totals of the
 //      chunks before its own (a few loads per lane) to get the chunk's absolute
-//      start, stages the tile's contiguous slice of `values` into LDS with 16-byte
-//      loads, scans the 64 word popcounts across lanes (DPP), and then, in 8 steps
+//      start, brings the tile's contiguous slice of `values` straight from memory
+//      into LDS (16 bytes per lane and load), scans the 64 word popcounts across
+//      lanes (DPP), and then, in 8 steps
 //      of 512 elements, every lane turns one bitmap byte into 8 output elements
 //      (8 LDS reads at rank-within-byte offsets, masked by the bits) and issues one
 //      16-byte store, so a wave writes 1 KiB of contiguous dense output per store
 //      instruction.
 //
-// The same tile expander, fed differently or draining into a different sink, gives
-// the row-subset kernel (Section 4.2's selective load), the matrix-vector product on
-// the compressed form, and - run backwards, as a scatter - the pack step of the
-// device-side compressor (Algorithm 1).  The element width (2 bytes, or 1 for the
-// 8-bit variant of Section 4.2) is a template parameter throughout.
+// The same tile expander, fed differently, gives the row-subset kernel (Section 4.2's
+// selective load) and - run backwards, as a scatter - the pack step of the device-side
+// compressor (Algorithm 1).  The element width (2 bytes, or 1 for the 8-bit variant of
+// Section 4.2) is a template parameter throughout.  The products on the compressed form
+// (here the matrix-vector one; the small-batch one has a file of its own) expand in
+// registers instead: a bitmap byte's values are one 16-byte window of `values`, read
+// straight from memory and put in place with byte permutes.
+//
+// One rule shaped all of these kernels: a load under a per-lane test whose result is used
+// after the test is waited for on the spot, so several of them in a row are as many trips
+// to memory.  Loads are therefore either unconditional (behind one wave-uniform test, or
+// from a clamped index, with the exceptional tiles in a loop of their own) or go straight
+// to LDS.
 //
 // The path is bound by memory traffic (2 bytes written, 1/8 + 2p bytes read per
 // element), so there is no matrix-core work here; all arithmetic on the format is
