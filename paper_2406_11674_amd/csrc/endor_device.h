@@ -13,6 +13,18 @@ namespace endor_device {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// A byte address known to lie in global memory, as a pointer the compiler knows to be global:
+// a load through a pointer made from an integer is otherwise a FLAT instruction, which also
+// counts as an LDS operation, so every wait for an LDS read waits for those loads as well.
+template <class T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T *global_ptr(uintptr_t a) {
+    return reinterpret_cast<const __attribute__((address_space(1))) T *>(a);
+}
+template <class T>
+__device__ __forceinline__ __attribute__((address_space(1))) T *global_ptr_mut(uintptr_t a) {
+    return reinterpret_cast<__attribute__((address_space(1))) T *>(a);
+}
+
 template <int kCtrl, int kRowMask>
 __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t x) {
     // lanes without a source, and rows masked off, receive 0
@@ -167,8 +179,8 @@ __device__ __forceinline__ bool windows_inside(uintptr_t first, uintptr_t last, 
 __device__ __forceinline__ WindowLoad window_issue(uintptr_t p) {
     const uintptr_t a = p & ~uintptr_t(3);
     WindowLoad L;
-    L.d = *reinterpret_cast<const u32x4_a4 *>(a);
-    L.d4 = *reinterpret_cast<const uint32_t *>(a + 16);
+    L.d = *global_ptr<u32x4_a4>(a);
+    L.d4 = *global_ptr<uint32_t>(a + 16);
     return L;
 }
 
@@ -189,7 +201,7 @@ __device__ __forceinline__ u32x4 window_guarded(uintptr_t p, uintptr_t vbeg, uin
     for (int j = 0; j < 8; ++j) {
         const uintptr_t q = p + 2 * j;
         uint32_t v = 0;
-        if (q >= vbeg && q + 2 <= vend) v = *reinterpret_cast<const uint16_t *>(q);
+        if (q >= vbeg && q + 2 <= vend) v = *global_ptr<uint16_t>(q);
         d[j >> 1] |= v << (16 * (j & 1));
     }
     u32x4 w;

@@ -54,6 +54,8 @@ namespace {
 
 using endor_device::chunk_base;
 using endor_device::dpp_or_zero;
+using endor_device::global_ptr;
+using endor_device::global_ptr_mut;
 using endor_device::load_to_lds16;
 using endor_device::window_finish;
 using endor_device::window_guarded;
@@ -235,14 +237,14 @@ struct alignas(16) WaveScratch {
 template <int E>
 __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uintptr_t vend) {
     // values are read once: streamed past the caches (the bitmap, read by both kernels, stays cacheable)
-    if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    if (p >= vbeg && p + 16 <= vend) return __builtin_nontemporal_load(global_ptr<u32x4>(p));
     uint32_t d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int j = 0; j < 16 / E; ++j) {
         const uintptr_t q = p + E * j;
         uint32_t v = 0;
         if (q >= vbeg && q + E <= vend)
-            v = (E == 2) ? uint32_t(*reinterpret_cast<const uint16_t *>(q)) : uint32_t(*reinterpret_cast<const uint8_t *>(q));
+            v = (E == 2) ? uint32_t(*global_ptr<uint16_t>(q)) : uint32_t(*global_ptr<uint8_t>(q));
         d[(E * j) >> 2] |= v << (8 * ((E * j) & 3));
     }
     u32x4 r;
@@ -474,19 +476,18 @@ __global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
 // words, with everything past the segment (or past the bitmap) cleared.
 __device__ __forceinline__ uint64_t segment_word(const uint64_t *bitmap, int64_t nwords, int64_t e,
                                                  uint32_t nbits, uint32_t lane) {
-    uint64_t word = 0;
-    if (lane * 64 < nbits) {
-        const int64_t w0 = (e >> 6) + lane;
-        const uint32_t bs = static_cast<uint32_t>(e & 63);
-        const uint64_t lo = w0 < nwords ? bitmap[w0] : 0;
-        word = lo >> bs;
-        if (bs != 0) {
-            const uint64_t hi = w0 + 1 < nwords ? bitmap[w0 + 1] : 0;
-            word |= hi << (64 - bs);
-        }
-        const uint32_t rem = nbits - lane * 64;  // bits of this lane that belong to the segment
-        if (rem < 64) word &= (uint64_t(1) << rem) - 1;
-    }
+    // Both loads are unconditional, from indices clamped into the bitmap, and the cases are
+    // sorted out with selects afterwards: under a test each load would be waited for on the
+    // spot, and a caller that fetches the next segment's word ahead would gain nothing.
+    const int64_t w0 = (e >> 6) + lane;
+    const uint32_t bs = static_cast<uint32_t>(e & 63);
+    const int64_t last = nwords - 1;  // nwords >= 1: the callers have at least one element
+    const uint64_t lo = bitmap[w0 < last ? w0 : last];
+    const uint64_t hi = bitmap[w0 + 1 < last ? w0 + 1 : last];
+    uint64_t word = (w0 < nwords ? lo : 0) >> bs;
+    word |= ((w0 + 1 < nwords ? hi : 0) << 1) << (63 - bs);  // hi << (64 - bs), and nothing when bs is 0
+    const uint32_t have = lane * 64 < nbits ? nbits - lane * 64 : 0u;  // bits of this lane that belong to the segment
+    if (have < 64) word &= (uint64_t(1) << have) - 1;
     return word;
 }
 
@@ -821,11 +822,10 @@ __global__ __launch_bounds__(64 * kGemvWaves) void endor_gemv_f16_kernel(GemvPar
             }
         }
     };
-    auto row_word = [&](int64_t c0) -> uint64_t {
+    auto row_word = [&](int64_t c0) -> uint64_t {  // no branch: a segment that does not exist has no bits
         const int64_t left = G.cols - c0;
-        if (!row_ok || left <= 0) return 0;
-        return segment_word(G.bitmap, nwords, row_bit + c0, left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg),
-                            lane);
+        const uint32_t nbits = (!row_ok || left <= 0) ? 0u : left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg);
+        return segment_word(G.bitmap, nwords, row_bit + c0, nbits, lane);
     };
 
     if (G.cols > 0) load_x(0, 0);
@@ -1073,16 +1073,16 @@ __global__ __launch_bounds__(64) void endor_pack_kernel(CompressParams C) {
         const bool inside = el0 >= shift && el0 + Sh::kLaneElems <= shift + cnt &&
                             static_cast<int64_t>(el0 + Sh::kLaneElems - shift) <= room;
         if (inside) {
-            *reinterpret_cast<u32x4 *>(a16 + 16 * uintptr_t(ch)) = S.stage[ch];
+            *global_ptr_mut<u32x4>(a16 + 16 * uintptr_t(ch)) = S.stage[ch];
         } else {
 #pragma unroll
             for (int j = 0; j < Sh::kLaneElems; ++j) {
                 const uint32_t el = el0 + j;
                 if (el >= shift && el < shift + cnt && static_cast<int64_t>(el - shift) < room) {
                     if (E == 2)
-                        reinterpret_cast<uint16_t *>(a16)[el] = reinterpret_cast<const uint16_t *>(S.stage)[el];
+                        global_ptr_mut<uint16_t>(a16)[el] = reinterpret_cast<const uint16_t *>(S.stage)[el];
                     else
-                        reinterpret_cast<uint8_t *>(a16)[el] = reinterpret_cast<const uint8_t *>(S.stage)[el];
+                        global_ptr_mut<uint8_t>(a16)[el] = reinterpret_cast<const uint8_t *>(S.stage)[el];
                 }
             }
         }
