@@ -110,6 +110,9 @@ struct MatParams {
 
 struct BatchParams {
     MatParams m[ENDOR_MAX_BATCH];
+    // the matrices' chunk_begin again, side by side: a wave finds its matrix from one scalar load
+    // of these instead of walking the descriptors (entries past `count` hold 0xffffffff)
+    uint32_t first_chunk[ENDOR_MAX_BATCH];
     int count;
 };
 
@@ -124,7 +127,8 @@ __device__ __forceinline__ uint64_t load_word_guarded(const uint64_t *bitmap, in
 
 __device__ __forceinline__ int find_matrix(const BatchParams &P, uint32_t chunk) {
     int mi = 0;
-    for (int i = 1; i < P.count; ++i) mi = (chunk >= P.m[i].chunk_begin) ? i : mi;
+#pragma unroll
+    for (int i = 1; i < ENDOR_MAX_BATCH; ++i) mi += (chunk >= P.first_chunk[i]) ? 1 : 0;  // ascending, so a count
     return mi;
 }
 
@@ -460,9 +464,10 @@ __global__ __launch_bounds__(64) void endor_expand_kernel(BatchParams P) {
     // the bitmap word first: its load is in flight while the table is looked up
     const uint64_t word = load_word_guarded(M.bitmap, tile * kTileWords + lane, full_words, tail_bits);
     const uint32_t *tile_off = M.tile_off + size_t(c) * kChunkStride + tl;
-    const uint64_t base = chunk_base(M.chunk_total, c, lane);
     const uint32_t o0 = tile_off[0];
-    const uint32_t cnt = tile_off[1] - o0;  // 1 bits in this tile
+    const uint32_t o1 = tile_off[1];
+    const uint64_t base = chunk_base(M.chunk_total, c, lane);
+    const uint32_t cnt = o1 - o0;  // 1 bits in this tile
     const int64_t e0 = tile * kTileElems;
     const int64_t left = n - e0;
     StoreSink<E, kAlignedOut, kBurst> sink;
@@ -1151,6 +1156,7 @@ endor_status fill_group(const endor_matrix *mats, int count, int need, int elem_
                         size_t ws_bytes, size_t *ws_off, Group *g) {
     const uintptr_t elem_mask = static_cast<uintptr_t>(elem_bytes - 1);
     g->P.count = 0;
+    for (int i = 0; i < ENDOR_MAX_BATCH; ++i) g->P.first_chunk[i] = 0xffffffffu;
     g->chunks = 0;
     g->aligned_out = true;
     g->elems = 0;
@@ -1181,6 +1187,7 @@ endor_status fill_group(const endor_matrix *mats, int count, int need, int elem_
         M.n = n;
         M.nnz = m.nnz;
         M.chunk_begin = g->chunks;
+        g->P.first_chunk[g->P.count - 1] = g->chunks;
         M.nchunks = nc;
         g->chunks += nc;
         g->elems += n;
@@ -1317,6 +1324,7 @@ extern "C" endor_status endor_check_batch(const endor_matrix *mats, int count, c
         // chunk_begin carries the matrix's index inside the batch for the kernel
         BatchParams P;
         P.count = nb;
+        for (int i = 0; i < ENDOR_MAX_BATCH; ++i) P.first_chunk[i] = 0xffffffffu;  // not used by the check kernel
         for (int i = 0; i < nb; ++i) {
             const endor_matrix &m = mats[b + i];
             const int64_t n = m.rows * m.cols;
