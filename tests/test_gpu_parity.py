@@ -970,6 +970,47 @@ def test_decompress_batch_in_a_hip_graph_replays_correctly():
             assert np.array_equal(o.cpu().numpy().view(np.uint16), e), f"replay {rep}"
 
 
+def test_products_in_a_hip_graph_replay_correctly():
+    """Both products captured into one graph (they allocate nothing and never synchronise) and
+    replayed on fresh right-hand sides, with eager work and synchronisation between the replays."""
+    rows, cols, nb = 300, 4099, 5
+    w = synth.pruned_fp16(rows, cols, 0.5, seed=71)
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    tab, ro = endor.build_offsets(m, row_offsets=True)
+    x = torch.zeros(cols, dtype=torch.float16, device="cuda")
+    X = torch.zeros((nb, cols), dtype=torch.float16, device="cuda")
+    y = torch.empty(rows, dtype=torch.float32, device="cuda")
+    Y = torch.empty((nb, rows), dtype=torch.float32, device="cuda")
+    sc = torch.empty(max(256, endor.gemm_scratch_bytes(rows, cols, nb)), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside capture
+        endor.gemv_f16(m, ro, x, y=y, stream=side)
+        endor.gemm_f16(m, tab, X, Y=Y, scratch=sc, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        endor.gemv_f16(m, ro, x, y=y, stream=torch.cuda.current_stream())
+        endor.gemm_f16(m, tab, X, Y=Y, scratch=sc, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        x16 = np.random.default_rng(100 + rep).standard_normal(cols).astype(np.float16)
+        X16 = np.random.default_rng(200 + rep).standard_normal((nb, cols)).astype(np.float16)
+        x.copy_(torch.from_numpy(x16.view(np.int16)).cuda().view(torch.float16))
+        X.copy_(torch.from_numpy(X16.view(np.int16)).cuda().view(torch.float16))
+        y.fill_(float("nan"))
+        Y.fill_(float("nan"))
+        sc.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = orc.gemv_f16(rows, cols, c.bitmap, c.values, x16)
+        assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= _gemv_tolerance(w, x16, cols)), f"replay {rep}"
+        refm = orc.gemm_f16(rows, cols, c.bitmap, c.values, X16)
+        assert np.all(np.abs(Y.cpu().numpy().astype(np.float64) - refm) <= _gemm_tolerance(w, X16, cols)), f"replay {rep}"
+
+
 # ---------------------------------------------------------------------------
 # more than 2^32 elements / values: 64-bit indexing everywhere
 # ---------------------------------------------------------------------------
