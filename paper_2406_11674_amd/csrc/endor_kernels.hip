@@ -838,7 +838,6 @@ __global__ __launch_bounds__(64 * kGemvWaves) void endor_gemv_f16_kernel(GemvPar
     uint32_t buf = 0;
     for (int64_t c0 = 0; c0 < G.cols; c0 += kGemvSeg, buf ^= 1u) {
         const int64_t left = G.cols - c0;
-        const uint32_t nbits = left < kGemvSeg ? static_cast<uint32_t>(left) : uint32_t(kGemvSeg);
         // this thread's piece of the segment's x has landed; after the barrier all of them have,
         // and every wave is through the previous segment (whose x the next load overwrites)
         wait_loads_to_lds();
