@@ -375,12 +375,14 @@ __global__ __launch_bounds__(256) void endor_gemm_zero_kernel(float *__restrict_
     if (i < count) y[i] = 0.0f;
 }
 
-// Column ranges per row group.  The chip holds kResident workgroups at a time (five per compute
-// unit, by registers and LDS), so the launch runs in ceil(workgroups / kResident) waves of
-// workgroups, each as long as one workgroup: its rounds plus a start-up worth about two.  Pick
-// the split that minimises the product (measured on 28672 x 8192: 4 ranges 98 us, 6 ranges,
-// which spill into a third wave, 111 us), the smaller one on a tie.
-constexpr int64_t kResident = 256 * 5;
+// Column ranges per row group.  The chip holds kResident workgroups at a time (four per compute
+// unit: 104 registers give four waves per SIMD, and a workgroup puts one wave on each), so the
+// launch runs in ceil(workgroups / kResident) waves of workgroups, each as long as one
+// workgroup: its rounds plus a start-up worth about two.  Pick the split that minimises the
+// product (measured on 28672 x 8192: 4 ranges 98 us, 6 ranges, which spill into a third wave,
+// 111 us; on 8192 x 28672: 8 ranges, exactly one wave of workgroups, 84 us, 10 ranges 94 us),
+// the smaller one on a tie.
+constexpr int64_t kResident = 256 * 4;
 uint32_t choose_split(int64_t rows, int64_t cols) {
     const int64_t groups = (rows + kRows - 1) / kRows;
     const int64_t wgs = (groups + kGemmWaves - 1) / kGemmWaves;
