@@ -48,9 +48,11 @@ def test_h2d_pipeline_hides_decompression_under_the_copy():
             best = min(best, time.perf_counter() - t)
         return best
 
-    t_serial = best_of(serial)
+    t_serial = t_pipe = 1e9
     out.fill_(0x7FFF)
-    t_pipe = best_of(lambda: pipe.run(blobs, outs))
+    for _ in range(3):  # alternate, so that a drift of the box hits both alike
+        t_serial = min(t_serial, best_of(serial, 7))
+        t_pipe = min(t_pipe, best_of(lambda: pipe.run(blobs, outs), 7))
     print(f"copy then decompress {t_serial * 1e3:.3f} ms, pipeline over {len(blobs)} row blocks "
           f"{t_pipe * 1e3:.3f} ms", flush=True)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), orc.decompress(rows, cols, c.bitmap, c.values))
