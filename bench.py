@@ -14,8 +14,9 @@ Llama2-70B decoder layer; beside it the same line carries
   extras    the entry points beyond plain decompression (8-bit values, row / column
             subsets, device-side compressor, fused products), each against its own
             algorithmic byte count
-  ceilings  plain streaming kernels (write, read, copy, the 1.125:2 mix) on the same
-            box: what the memory system delivers for traffic of this shape
+  ceilings  plain streaming kernels (write, read, copy, the 1.125:2 mix, and the mixes of
+            the other densities and of 8-bit values) on the same box: what the memory
+            system delivers for traffic of this shape
 `--workload X --only` restricts the run to one workload (the form the rocprofv3
 summaries under profiles/ are made with).
 """
@@ -376,6 +377,33 @@ def ceilings_leg(torch, nbytes=1 << 30, reps=10):
         ms = a.elapsed_time(b) / reps
         res[name] = {"ms": round(ms, 4), "GB/s": round(moved / ms / 1e6, 1),
                      "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    # the read : write ratio of the other configurations, in 16-byte units read per 256 written
+    # (per element: 1/8 byte of bitmap + keep * E bytes of values read, E bytes written)
+    if hasattr(P, "endor_probe_mix"):
+        P.endor_probe_mix.restype = ctypes.c_int
+        P.endor_probe_mix.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                      ctypes.c_void_p, ctypes.c_void_p]
+        res["mix_by_ratio"] = {}
+        for name, e, keep in (("fp16_keep_0.1", 2, 0.1), ("fp16_keep_0.3", 2, 0.3), ("fp16_keep_0.5", 2, 0.5),
+                              ("fp16_keep_0.7", 2, 0.7), ("u8_keep_0.5", 1, 0.5)):
+            k = int(round(256 * (0.125 + keep * e) / e))
+            def fn():
+                rc = P.endor_probe_mix(k, src.data_ptr(), dst.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream)
+                assert rc == 0
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            a, b = _events(torch)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            moved = nbytes + nbytes * k // 256
+            res["mix_by_ratio"][name] = {"reads_per_256_written": k, "ms": round(ms, 4),
+                                         "GB/s": round(moved / ms / 1e6, 1),
+                                         "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBS, 4)}
     return res
 
 
