@@ -589,6 +589,14 @@ def test_compress_device_unaligned_dense_and_values():
     assert torch.all(vbuf[:3] == POISON) and torch.all(vbuf[3 + v.size:] == POISON)
 
 
+def test_compress_device_many_chunks():
+    """More chunks than lanes (so the sum of chunk totals takes several rounds) and a last
+    chunk with a single tile."""
+    _say("device compress, 66 chunks")
+    rows, cols = 16897, 4096                                  # 16897 tiles = 66 chunks + 1 tile
+    _check_device_compress(synth.pruned_fp16(rows, cols, 0.3, seed=21))
+
+
 def test_compress_device_full_size_down_proj():
     _say("device compress full size")
     w = synth.pruned_fp16(8192, 28672, 0.5, seed=synth.seed_for(4, 0))
