@@ -229,13 +229,28 @@ struct alignas(16) WaveScratch {
     // staging in 16-byte units: up to kLaneElems-1 elements of alignment slack in front, kCap
     // values, and kLaneElems-1 elements a lane may read past its last value (those reads are
     // masked off by the bits)
-    static constexpr int kStageChunks = (E * (2 * (kLaneElems - 1) + kCap) + 15) / 16;
+    // (8-bit values are read as dword pairs around a lane's values, up to 4 bytes further: one unit more)
+    static constexpr int kStageChunks = (E * (2 * (kLaneElems - 1) + kCap) + 15) / 16 + (E == 1 ? 1 : 0);
     static constexpr int kStageRounds = (kStageChunks + 63) / 64;
-    static constexpr uint32_t kMaxIndex = kStageChunks * (16 / E) - kLaneElems;  // last index a gather may start at
+    // last index a lane's values may start at
+    static constexpr uint32_t kMaxIndex = (kStageChunks - (E == 1 ? 1 : 0)) * (16 / E) - kLaneElems;
     u32x4 stage[kStageChunks];   // the tile's slice of `values`, from the 16-byte boundary below it
     uint64_t words[kTileWords];  // the tile's bitmap words
     uint32_t start[kTileWords];  // per word: index into `stage` (in elements) of its first value
+    // 8-bit values only: per 4-bit pattern the v_perm_b32 selector that moves the pattern's
+    // consecutive values to the positions of its 1 bits and zeroes the others
+    uint32_t nibble_sel[E == 1 ? 16 : 1];
 };
+
+// Selector for pattern n (bits 0..3): output byte k takes source byte popcount(n below k) when
+// bit k is set, and the constant zero (selector 0x0c) otherwise.
+__device__ __forceinline__ uint32_t nibble_selector(uint32_t n) {
+    uint32_t sel = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        sel |= (((n >> k) & 1u) ? uint32_t(__popc(n & ((1u << k) - 1))) : 0x0cu) << (8 * k);
+    return sel;
+}
 
 // 16 bytes of `values` at byte address p, with bytes outside [vbeg, vend) read as 0
 template <int E>
@@ -262,11 +277,6 @@ __device__ __forceinline__ u32x4 load_values16(uintptr_t p, uintptr_t vbeg, uint
 // 0xffff in the halves whose bit is set: bits 0,1 of `b` -> low, high half
 __device__ __forceinline__ uint32_t half_mask(uint32_t b) {
     return ((b & 1u) ? 0xffffu : 0u) | ((b & 2u) ? 0xffff0000u : 0u);
-}
-// 0xff in the bytes whose bit is set: bits 0..3 of `b`
-__device__ __forceinline__ uint32_t byte_mask(uint32_t b) {
-    return ((b & 1u) ? 0xffu : 0u) | ((b & 2u) ? 0xff00u : 0u) | ((b & 4u) ? 0xff0000u : 0u) |
-           ((b & 8u) ? 0xff000000u : 0u);
 }
 
 // Sink that writes the expanded tile to memory: a 16-byte non-temporal store per lane
@@ -338,14 +348,22 @@ __device__ __forceinline__ void expand_step(const WaveScratch<E, kCap> &S, int k
         d.z = (h[4] | (h[5] << 16)) & half_mask(bits >> 4);
         d.w = (h[6] | (h[7] << 16)) & half_mask(bits >> 6);
     } else {
-        const uint8_t *sp = reinterpret_cast<const uint8_t *>(S.stage) + s;
-        uint32_t h[16];
+        // 8-bit values: an output dword's four elements take consecutive values, so one read of the
+        // two dwords around them, a funnel shift and a byte permute replace four single-byte
+        // gathers (the 8-bit kernel was bound by vector ALU and LDS instructions, not by memory)
+        const uint32_t *sw = reinterpret_cast<const uint32_t *>(S.stage);
+        uint32_t o[4];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) h[j] = sp[__popc(bits & ((1u << j) - 1))];
-        d.x = (h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24)) & byte_mask(bits);
-        d.y = (h[4] | (h[5] << 8) | (h[6] << 16) | (h[7] << 24)) & byte_mask(bits >> 4);
-        d.z = (h[8] | (h[9] << 8) | (h[10] << 16) | (h[11] << 24)) & byte_mask(bits >> 8);
-        d.w = (h[12] | (h[13] << 8) | (h[14] << 16) | (h[15] << 24)) & byte_mask(bits >> 12);
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t at = s + __popc(bits & ((1u << (4 * q)) - 1));  // byte index of the dword's first value
+            const uint32_t lo = sw[at >> 2], hi = sw[(at >> 2) + 1];
+            const uint32_t x = __builtin_amdgcn_alignbyte(hi, lo, at & 3u);
+            o[q] = __builtin_amdgcn_perm(x, x, S.nibble_sel[(bits >> (4 * q)) & 15u]);
+        }
+        d.x = o[0];
+        d.y = o[1];
+        d.z = o[2];
+        d.w = o[3];
     }
     sink(k, (k * 64 + lane) * Sh::kLaneElems, d);
 }
@@ -378,6 +396,7 @@ __device__ __forceinline__ void expand_tile(WaveScratch<E, kCap> &S, uint32_t la
     //     bitmap word, loaded by the caller, may still be on its way
     const uintptr_t a16 = vaddr & ~uintptr_t(15);
     const uint32_t shift = static_cast<uint32_t>(vaddr - a16) / E;  // elements of slack in front
+    if (E == 1 && lane < 16) S.nibble_sel[lane] = nibble_selector(lane);
     cnt = cnt > kCap ? kCap : cnt;  // a stale or foreign table must not overrun the staging area
     const uint32_t nch = cnt ? (((shift + cnt) * E + 15) >> 4) : 0;  // < kStageChunks
     // the whole slice lies inside `values`: all tiles but the first and last of an array that
