@@ -532,9 +532,9 @@ struct RowsParams {
 // starts at an arbitrary bit position, so a lane's 64 bits are funnelled out of two
 // neighbouring bitmap words; its first value is row_offsets[row] plus the 1 bits of the
 // row's earlier segments, counted here from the bitmap.
-template <int E, bool kAlignedOut>
+template <int E, bool kAlignedOut, int kCap = kTileElems>
 __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
-    __shared__ WaveScratch<E> s_scratch;
+    __shared__ WaveScratch<E, kCap> s_scratch;
     const uint32_t lane = threadIdx.x;
     const int64_t r = blockIdx.x / R.segs;
     const uint32_t g = blockIdx.x % R.segs;
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(64) void endor_expand_rows_kernel(RowsParams R) {
     StoreSink<E, kAlignedOut, false> sink;
     sink.out = reinterpret_cast<uint8_t *>(R.out) + (r * R.cols + int64_t(g) * kTileElems) * E;
     sink.nvalid = nbits;
-    expand_tile<E>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend, sink);
+    expand_tile<E, kCap>(s_scratch, lane, word, vbeg + E * first, cnt, vbeg, vend, sink);
 }
 
 // ---------------------------------------------------------------- kernel 2c: selected columns
@@ -1518,8 +1518,15 @@ endor_status run_rows(int elem_bytes, int64_t rows, int64_t cols, const uint8_t 
     const bool aligned = (reinterpret_cast<uintptr_t>(d_out) & 15) == 0 && (cols * elem_bytes) % 16 == 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(static_cast<unsigned>(blocks));
+    // A selection is usually small (Section 4.2: the rows of the active neurons), so the kernel
+    // lives on how many waves a compute unit holds at once: when no more than 9 elements in 16 are
+    // kept overall, a staging area of 2304 values (a tile with more takes the step-by-step path)
+    // lets 29 waves share a unit instead of 17.
+    const bool small_stage = nnz <= (rows * cols / 16) * 9;
     if (elem_bytes == 2) {
-        if (aligned)
+        if (aligned && small_stage)
+            hipLaunchKernelGGL((endor_expand_rows_kernel<2, true, 2304>), grid, dim3(64), 0, s, R);
+        else if (aligned)
             hipLaunchKernelGGL((endor_expand_rows_kernel<2, true>), grid, dim3(64), 0, s, R);
         else
             hipLaunchKernelGGL((endor_expand_rows_kernel<2, false>), grid, dim3(64), 0, s, R);

@@ -473,6 +473,34 @@ def test_decompress_rows_matches_oracle(shape, wide):
         assert np.array_equal(out.cpu().numpy().view(expect.dtype), expect)
 
 
+def test_decompress_rows_dense_rows_inside_a_sparse_matrix():
+    """Overall sparse enough for the row kernel's smaller staging area (2304 values), with row
+    segments that exceed it: all 4096 set, 2305 (one over), exactly 2304 (the limit), and a dense
+    ragged last segment."""
+    rows, cols = 12, 2 * 4096 + 37
+    _say("rows: dense rows in a sparse matrix")
+    g = np.random.default_rng(91)
+    w = g.integers(1, 1 << 16, size=(rows, cols), dtype=np.uint32).astype(np.uint16)
+    w[g.random((rows, cols)) >= 0.1] = 0
+    w[2, :] = g.integers(1, 1 << 16, size=cols, dtype=np.uint32).astype(np.uint16)        # every segment full
+    for row, ones in ((4, 2305), (5, 2304)):
+        seg = np.zeros(4096, np.uint16)
+        seg[g.choice(4096, ones, replace=False)] = g.integers(1, 1 << 16, size=ones, dtype=np.uint32).astype(np.uint16)
+        w[row, 4096:8192] = seg
+    w[7, 8192:] = 0x3C00
+    assert np.count_nonzero(w) * 16 <= (rows * cols // 16) * 9 * 16
+    c = endor.compress(w)
+    m = endor.to_device(c)
+    sel_np = np.array([2, 4, 5, 7, 0, 11, 2], np.int64)
+    out = torch.full((sel_np.size, cols), POISON, dtype=torch.int16, device="cuda")
+    for _ in range(2):
+        endor.decompress_rows(m, torch.from_numpy(c.row_offsets).cuda(), torch.from_numpy(sel_np).cuda(), out=out)
+    torch.cuda.synchronize()
+    expect = orc.decompress_selected_rows(cols, sel_np, c.row_offsets, c.bitmap, c.values)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), expect)
+    assert np.array_equal(expect, w[sel_np])
+
+
 def test_decompress_rows_out_of_range_index_is_skipped():
     rows, cols = 12, 5000
     w = synth.pruned_fp16(rows, cols, 0.5, seed=77)
