@@ -1194,6 +1194,79 @@ def test_decompress_cols_full_size_down_proj():
     assert np.array_equal(out.cpu().numpy().view(np.uint16), expect[:, sel_np])
 
 
+# ---------------------------------------------------------------------------
+# seeded sweep: random shapes and densities through every entry point.  The densities sit on both
+# sides of the points where the host switches kernels (one element in five for the store-dominated
+# expander, nine in sixteen for the row kernel's staging area) and at the two ends.
+# ---------------------------------------------------------------------------
+SWEEP_KEEPS = [0.0, 0.02, 0.1, 0.19, 0.21, 0.5, 0.55, 0.58, 0.9, 1.0]
+
+
+@pytest.mark.parametrize("case", range(100))
+def test_seeded_sweep_through_every_entry_point(case):
+    g = np.random.default_rng(1000 + case)
+    rows = int(g.integers(1, 200))
+    cols = int(g.choice([g.integers(1, 300), g.integers(4000, 4200), g.integers(8100, 8300), g.integers(1, 20000)]))
+    keep = SWEEP_KEEPS[case % len(SWEEP_KEEPS)]
+    wide = bool(g.integers(0, 2))
+    _say(f"sweep case={case} shape=({rows}, {cols}) keep={keep} wide={wide}")
+    if wide:
+        w = g.integers(1, 1 << 16, size=(rows, cols), dtype=np.uint32).astype(np.uint16)
+    else:
+        w = g.integers(1, 256, size=(rows, cols), dtype=np.uint16).astype(np.uint8)
+    w[g.random((rows, cols)) >= keep] = 0
+    dt = torch.int16 if wide else torch.uint8
+    c = endor.compress(w)
+    b, v, r = orc.compress(w)
+    assert np.array_equal(c.bitmap[: b.size], b) and np.array_equal(c.values, v) and np.array_equal(c.row_offsets, r)
+    m = endor.to_device(c)
+    ro = torch.from_numpy(c.row_offsets).cuda()
+
+    # Algorithm 2
+    expect = orc.decompress(rows, cols, c.bitmap, c.values)
+    assert np.array_equal(expect, w.view(expect.dtype))
+    out = torch.full((rows, cols), 0x5A, dtype=dt, device="cuda")
+    endor.decompress(m, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(expect.dtype), expect)
+
+    # selected rows and columns
+    rsel = g.integers(0, rows, size=max(1, rows // 3)).astype(np.int64)
+    got = endor.decompress_rows(m, ro, torch.from_numpy(rsel).cuda())
+    csel = g.integers(0, cols, size=max(1, cols // 5)).astype(np.int64)
+    gotc = torch.full((rows, csel.size), 0x5A, dtype=dt, device="cuda")
+    endor.decompress_cols(m, ro, torch.from_numpy(csel).cuda(), out=gotc)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(expect.dtype), expect[rsel])
+    assert np.array_equal(gotc.cpu().numpy().view(expect.dtype), expect[:, csel])
+
+    # Algorithm 1 on the device
+    dm, _, dro = endor.compress_device(torch.from_numpy(w.view(np.int16) if wide else w).cuda(), row_offsets=True)
+    torch.cuda.synchronize()
+    assert dm.nnz == v.size
+    assert np.array_equal(dm.bitmap.cpu().numpy()[: b.size], b)
+    assert np.array_equal(dm.values.cpu().numpy().view(v.dtype), v)
+    assert np.array_equal(dro.cpu().numpy(), r)
+
+    # the products (fp16 only): values reinterpreted as fp16, non-finite patterns cleared first
+    if wide:
+        wf = w.copy()
+        wf[(wf & 0x7C00) == 0x7C00] = 0x3C00
+        cf = endor.compress(wf)
+        mf = endor.to_device(cf)
+        rof = torch.from_numpy(cf.row_offsets).cuda()
+        x16 = g.standard_normal(cols).astype(np.float16)
+        y = endor.gemv_f16(mf, rof, torch.from_numpy(x16).cuda())
+        torch.cuda.synchronize()
+        ref = orc.gemv_f16(rows, cols, cf.bitmap, cf.values, x16)
+        assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= _gemv_tolerance(wf, x16, cols))
+        nb = int(g.integers(1, 17))
+        X16 = g.standard_normal((nb, cols)).astype(np.float16)
+        gotY = _gpu_gemm(cf, X16)
+        refY = orc.gemm_f16(rows, cols, cf.bitmap, cf.values, X16)
+        assert np.all(np.abs(gotY - refY) <= _gemm_tolerance(wf, X16, cols))
+
+
 def test_concurrent_calls_on_two_streams_with_distinct_workspaces():
     """The library keeps no state between calls: two host threads, two streams, two workspaces."""
     import threading
